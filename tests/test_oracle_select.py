@@ -1,0 +1,145 @@
+"""Pins for the selector oracle (Alg. 2, Lemma 3.1, Theorems 1 and 2).  CPU only."""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import fast, pods_oracle as po
+from paper_2504_13818_amd import inputs
+
+
+def _var(vals):
+    xs = [Fraction(float(v)) for v in vals]
+    m = len(xs)
+    mu = sum(xs) / m
+    return sum((x - mu) ** 2 for x in xs) / m      # two-pass form, unlike the oracle's
+
+
+def _cases(rng, n):
+    yield rng.integers(0, 2, n).astype(np.float32)                       # binary
+    yield (rng.integers(0, 5, n) * 0.25).astype(np.float32)             # tag-count style levels
+    yield rng.standard_normal(n).astype(np.float32)                      # continuous
+    yield (rng.integers(0, 2, n) + np.float32(0.1) * rng.integers(0, 2, n)).astype(np.float32)
+    yield np.full(n, np.float32(0.3))                                    # all equal, non-dyadic
+    yield (rng.integers(0, 3, n) * 0.5 - 0.5).astype(np.float32)        # has negatives and zero
+
+
+def test_hand_worked_cases():
+    # sorted 1,1,2,3,4,5,6,9 ; m=3 : Var{1,1,2}=2/9, Var{1,1,9}=128/9, Var{1,6,9}=98/9, Var{5,6,9}=26/9
+    r = np.array([3, 1, 4, 1, 5, 9, 2, 6], dtype=np.float32)
+    assert po.select_exact(r, 3) == ([1, 3, 5], 1)
+    # all equal: the m lowest-indexed, k = 0
+    assert po.select_exact(np.full(7, 0.7, dtype=np.float32), 3) == ([0, 1, 2], 0)
+    # binary, alternating: zeros at 1,3,5 ones at 0,2,4 ; m=4 -> two lowest zeros, two highest ones
+    r = np.array([1, 0, 1, 0, 1, 0], dtype=np.float32)
+    assert po.select_exact(r, 4) == ([1, 3, 2, 4], 2)
+    # m odd, binary: k=1 and k=2 tie exactly (2/9); the scan keeps the smaller k
+    r = np.array([0, 0, 0, 1, 1, 1], dtype=np.float32)
+    assert po.select_exact(r, 3) == ([0, 1, 5], 1)
+    # -0.0 ties with +0.0 and is ordered by index
+    r = np.array([0.0, -0.0, 1.0], dtype=np.float32)
+    assert po.select_exact(r, 2) == ([0, 2], 1)
+    # sorted -1(i2), 0(i0), 0(i1): k=0 {-1,0} and k=1 {-1,0} are the same multiset -> k stays 0
+    r = np.array([-0.0, 0.0, -1.0], dtype=np.float32)
+    assert po.select_exact(r, 2) == ([2, 0], 0)
+    # extremes far apart on one side only: 0,0,0,0,10 m=2 -> {0,10}
+    assert po.select_exact(np.array([0, 0, 10, 0, 0], dtype=np.float32), 2) == ([0, 2], 1)
+
+
+@pytest.mark.parametrize("n", [5, 8, 12])
+def test_brute_force_definition(n):
+    """Sec. 3.3: S = argmax Var over all C(n, m) subsets; exact rationals."""
+    rng = np.random.default_rng(100 + n)
+    for r in _cases(rng, n):
+        for m in sorted({1, 2, 3, n // 2, n - 1}):
+            if not 0 < m <= n:
+                continue
+            best = max(_var(r[list(S)]) for S in itertools.combinations(range(n), m))
+            assert po.max_variance_bruteforce(r, m) == best
+            idx, k = po.select_exact(r, m)
+            assert len(set(idx)) == m
+            assert _var(r[idx]) == best
+            idx2, k2 = po.select_prefix(r, m)
+            assert (idx2, k2) == (idx, k)
+            idx3, k3, _ = fast.select(r[None, :], m)
+            assert (list(idx3[0]), int(k3[0])) == (idx, k)
+
+
+def test_smallest_k_among_maximisers():
+    """Alg. 2 replaces only on a strictly larger variance, scanning k upward from 0."""
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        n = int(rng.integers(3, 11))
+        m = int(rng.integers(1, n + 1))
+        r = (rng.integers(0, 3, n) * 0.5).astype(np.float32)
+        ind = po.stable_argsort(r)
+        vars_ = [_var(r[ind[: m - k] + ind[n - k:]]) for k in range(m + 1)]
+        want_k = vars_.index(max(vars_))
+        idx, k = po.select_exact(r, m)
+        assert k == want_k and idx == ind[: m - k] + ind[n - k:]
+        assert po.select_prefix(r, m) == (idx, k)
+
+
+def test_lemma_structure_and_tie_order():
+    """Lemma 3.1: the optimum is the (m-k) lowest and k highest of the sorted order; with the
+    (reward, index) order the low part takes the lowest indices among equals, the high part the
+    highest."""
+    rng = np.random.default_rng(11)
+    for _ in range(100):
+        n = int(rng.integers(4, 40))
+        m = int(rng.integers(1, n + 1))
+        r = (rng.integers(0, 4, n) / 3).astype(np.float32)
+        idx, k = po.select_prefix(r, m)
+        order = sorted(range(n), key=lambda i: (r[i], i))
+        assert idx == order[: m - k] + order[n - k:]
+        lo, hi = idx[: m - k], idx[m - k:]
+        for part, pick_low in ((lo, True), (hi, False)):
+            if not part:
+                continue
+            edge = r[part[-1]] if pick_low else r[part[0]]
+            same = [i for i in range(n) if r[i] == edge]
+            chosen = [i for i in part if r[i] == edge]
+            assert chosen == (same[: len(chosen)] if pick_low else same[len(same) - len(chosen):])
+
+
+def test_theorem2_binary_closed_form():
+    """Theorem 2 (m even, binary rewards): m/2 ones and m/2 zeros when both are plentiful,
+    else every rollout of the scarcer class."""
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        n = int(rng.integers(2, 64))
+        m = 2 * int(rng.integers(1, n // 2 + 1))
+        r = (rng.random(n) < rng.random()).astype(np.float32)
+        c1 = int(r.sum())
+        c0 = n - c1
+        idx, k = po.select_prefix(r, m)
+        ones_kept = int(r[idx].sum())
+        assert ones_kept == min(c1, max(m // 2, m - c0))
+        idxc, kc, _ = fast.select(r[None, :], m)
+        assert list(idxc[0]) == idx and int(kc[0]) == k
+
+
+def test_exact_vs_prefix_vs_c_on_config_shapes():
+    for cfg, B in ((0, None), (1, None), (2, None), (4, None), (3, 48)):
+        r = inputs.rewards(cfg, B=B)
+        m = inputs.CONFIGS[cfg]["m"]
+        ie, ke = po.select_batch(r, m, exact=True)
+        ip, kp = po.select_batch(r, m, exact=False)
+        ic, kc, _ = fast.select(r, m)
+        assert np.array_equal(ie, ip) and np.array_equal(ke, kp)
+        assert np.array_equal(ie, ic) and np.array_equal(ke, kc)
+
+
+def test_m_equals_n_and_m_one():
+    r = np.array([0.5, 0.25, 0.75, 0.25], dtype=np.float32)
+    assert po.select_exact(r, 4) == ([1, 3, 0, 2], 0)
+    assert po.select_exact(r, 1) == ([1], 0)
+    ic, kc, _ = fast.select(r[None], 4)
+    assert list(ic[0]) == [1, 3, 0, 2] and kc[0] == 0
+
+
+def test_c_oracle_rejects_bad_arguments():
+    r = np.zeros((2, 4), dtype=np.float32)
+    with pytest.raises(ValueError):
+        fast.select(r, 5)
