@@ -1,0 +1,128 @@
+/* pods.h - C ABI of the PODS hot path on one AMD MI355X (gfx950).
+ *
+ * PODS ("Policy Optimization with Down-Sampling") generates n rollouts per prompt, keeps m < n
+ * of them by a down-sampling rule, and runs the GRPO policy update on the kept ones only.
+ * This library is the device side of that update's data-parallel hot path:
+ *
+ *   pods_select               max-variance down-sampling, batched over prompt groups
+ *                             (Sec. 3.3: definition, Lemma 3.1, Algorithm 2, Theorem 1)
+ *   pods_advantage            group-normalised advantages over the kept rollouts (Sec. 3.2)
+ *   grpo_token_loss_fwd_bwd   the GRPO-PODS objective L_PODS(theta, S) (Sec. 3.2, and L_GRPO in
+ *                             Sec. 3.1) taken through the policy's last layer: the lm_head
+ *                             projection, log-softmax, importance ratio, clipped surrogate, and
+ *                             the gradients w.r.t. the hidden states and the lm_head weight,
+ *                             without ever holding the [tokens, vocab] logits in memory.
+ *
+ * Conventions for every entry point
+ *   - Every pointer is a DEVICE pointer unless marked "host".  `stream` is a hipStream_t passed
+ *     as void* (NULL = the default stream).  Calls only enqueue work on `stream`: no host
+ *     synchronisation, no host read of device data, no device allocation.
+ *   - The caller owns every buffer, including the workspace.  Outputs are overwritten, inputs
+ *     are never modified.  Arrays are dense, row-major, 0-based indices (the paper is 1-based).
+ *   - The return value is a pods_status; nothing throws or aborts across this boundary.
+ *     Conditions the host can see (null pointers, non-positive sizes, m > n, a workspace that
+ *     is too small, a shape no kernel variant covers) are reported before anything is launched.
+ *     Conditions that live in device data (NaN or infinite rewards, a token id outside [0, V),
+ *     a length outside [0, T]) are not checked and give undefined results.
+ *   - pods_last_error() returns a host string describing the last failure on this thread.
+ */
+#ifndef PODS_H_
+#define PODS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PODS_OK = 0,
+    PODS_ERR_INVALID_ARG = 1,  /* null pointer, size <= 0, m > n, negative clip_eps, ...        */
+    PODS_ERR_UNSUPPORTED = 2,  /* a shape outside what the kernels cover (limits stated below)  */
+    PODS_ERR_WORKSPACE = 3,    /* workspace pointer null / misaligned / smaller than required   */
+    PODS_ERR_RUNTIME = 4       /* a HIP launch failed; pods_last_error() has the HIP message    */
+} pods_status;
+
+typedef enum { PODS_F32 = 0, PODS_BF16 = 1 } pods_dtype;
+
+/* Max-variance down-sampling D_maxv (Sec. 3.3).  For each of B prompt groups, chooses the m of
+ * n rewards whose (population) variance is maximal.  By Lemma 3.1 the optimum is the (m-k)
+ * lowest plus the k highest rewards of the sorted order for some k; Algorithm 2 scans k = 0..m
+ * and keeps a candidate only when its variance is strictly larger, so the smallest maximising k
+ * wins; Theorem 1's prefix sums make each candidate O(1).
+ *
+ * Tie rule (the paper leaves it open): the sort order is ascending (reward, index), -0.0 equal
+ * to +0.0.  Hence among equal rewards the low part takes the lowest indices, the high part the
+ * highest.  Candidate variances are compared as m*sum(x^2) - (sum x)^2 in double precision; a
+ * candidate whose multiset equals the previous candidate's is never preferred.
+ *
+ *   rewards  [B, n] float32, in
+ *   sel_idx  [B, m] int32, out: ind[0 .. m-k) followed by ind[n-k .. n) of the sorted order
+ *   sel_k    [B]    int32, out: the chosen k; may be NULL
+ *   1 <= m <= n <= 4096 (PODS_ERR_UNSUPPORTED above that).  m == n is accepted (k = 0).
+ */
+pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m,
+                        int32_t* sel_idx, int32_t* sel_k, void* stream);
+
+/* Advantages over the kept rollouts (Sec. 3.2): a_{S,i} = (r_i - mu_S) / (sigma_S + std_eps)
+ * with mu_S, sigma_S the mean and population standard deviation of the m kept rewards, so each
+ * group's advantages sum to zero.  A group whose kept rewards are all equal gets exactly 0.
+ *
+ *   rewards  [B, n] float32, in
+ *   sel_idx  [B, m] int32, in (values in [0, n))
+ *   adv      [B, m] float32, out, in sel_idx's order; read as adv[R], R = B*m, by the loss
+ *   1 <= m <= n, m <= 4096.
+ */
+pods_status pods_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
+                           int32_t m, float std_eps, float* adv, void* stream);
+
+/* Bytes of workspace grpo_token_loss_fwd_bwd wants for these sizes (a recommendation: any
+ * workspace of at least grpo_token_loss_workspace_min_bytes works, a larger one lets the
+ * backward pass use larger vocabulary chunks).  Returns 0 for invalid sizes. */
+size_t grpo_token_loss_workspace_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
+size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
+
+/* GRPO-PODS token loss, forward and backward (objective of Sec. 3.2; with S = all rollouts it
+ * is L_GRPO of Sec. 3.1).  For R kept rollouts (R = B*m over a batch of prompts, concatenated
+ * as Sec. 3.2 prescribes), with logits z = W_lm h, log pi(y) = z_y - logsumexp(z),
+ * rho = exp(log pi(y) - old_logp):
+ *
+ *   loss = -(1/R) sum_i (1/len_i) sum_{t < len_i} min[ rho_it a_i, clip(rho_it, 1-eps, 1+eps) a_i ]
+ *
+ * (minus the objective, which the paper maximises).  old_logp is a constant (pi_theta_fixed).
+ * Gradient flows through a token iff the unclipped term is the selected one, i.e. unless
+ * (a > 0 and rho > 1+eps) or (a < 0 and rho < 1-eps).  A rollout of length 0 contributes 0 and
+ * still counts in R.
+ *
+ *   hidden    [R, T, d] dt, in: last-layer hidden state per position (right-padded rollouts)
+ *   w_lm      [V, d]    dt, in: lm_head weight, logits = hidden . w_lm^T, no bias
+ *   tokens    [R, T] int32, in: generated token per position, in [0, V)
+ *   old_logp  [R, T] float32, in: log pi_theta_fixed of that token
+ *   adv       [R]    float32, in: a_{S,i}
+ *   lengths   [R]    int32, in: valid prefix length in [0, T]; NULL = every rollout has T
+ *   clip_eps  >= 0;  grad_scale multiplies both gradients (upstream d/d loss, or a global 1/R fix)
+ *   loss      [1]    float32, out (device)
+ *   logp_out  [R, T] float32, out, log pi_theta(y) at valid positions, 0 at padded; may be NULL
+ *   d_hidden  [R, T, d] float32, out: grad_scale * d loss / d hidden; padded rows are zero
+ *   d_w_lm    [V, d]    float32, out: grad_scale * d loss / d w_lm
+ *   workspace 256-byte aligned device buffer of workspace_bytes; contents undefined after the call
+ *
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; softmax statistics are
+ * fp32; the per-logit gradient is rounded to bf16 before the two gradient contractions.
+ * fp32 inputs use fp32 arithmetic throughout.  d <= 16384.
+ */
+pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                    const float* old_logp, const float* adv, const int32_t* lengths,
+                                    int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
+                                    float clip_eps, float grad_scale, float* loss, float* logp_out,
+                                    float* d_hidden, float* d_w_lm, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
+/* Host string for the last error on the calling thread; valid until the next failing call. */
+const char* pods_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PODS_H_ */

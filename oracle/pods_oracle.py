@@ -155,7 +155,8 @@ def token_rows(h: np.ndarray, w: np.ndarray, y: np.ndarray, old_logp: np.ndarray
     dz[K, V] = d loss / d logits, d_h[K, d]; all float64.
     """
     K = h.shape[0]
-    z = (h.astype(gemm_dtype) @ w.astype(gemm_dtype).T).astype(np.float64)      # logits
+    wg = w.astype(gemm_dtype, copy=False)
+    z = (h.astype(gemm_dtype, copy=False) @ wg.T).astype(np.float64)      # logits
     zmax = z.max(axis=1, keepdims=True)
     lse = zmax[:, 0] + np.log(np.exp(z - zmax).sum(axis=1))
     rows = np.arange(K)
@@ -172,7 +173,7 @@ def token_rows(h: np.ndarray, w: np.ndarray, y: np.ndarray, old_logp: np.ndarray
     p = np.exp(z - lse[:, None])                                               # softmax
     dz = -g[:, None] * p
     dz[rows, y] += g
-    d_h = (dz.astype(gemm_dtype) @ w.astype(gemm_dtype)).astype(np.float64)
+    d_h = (dz.astype(gemm_dtype, copy=False) @ wg).astype(np.float64)
     return dict(logp=logp, obj=obj, g=g, dz=dz, d_h=d_h, lse=lse)
 
 
@@ -211,5 +212,5 @@ def grpo_token_loss(hidden: np.ndarray, w: np.ndarray, tokens: np.ndarray, old_l
         logp[bi, bt] = out["logp"]
         d_hidden[bi, bt] = out["d_h"]
         if want_dw:
-            d_w += (out["dz"].astype(gemm_dtype).T @ hb.astype(gemm_dtype)).astype(np.float64)
+            d_w += (out["dz"].astype(gemm_dtype, copy=False).T @ hb.astype(gemm_dtype, copy=False)).astype(np.float64)
     return dict(loss=loss, logp=logp, d_hidden=d_hidden, d_w=d_w)

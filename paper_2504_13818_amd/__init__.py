@@ -1,0 +1,16 @@
+"""PODS hot path on AMD MI355X: thin Python binding over the C ABI in include/pods.h.
+
+The functions here only marshal arguments (device pointers, sizes, the current HIP stream) into
+libpods_hip.so; every step of the path runs in the library's HIP kernels.  PyTorch is used for
+device memory and streams only.  There is no CPU fallback: if the library is missing or a call
+fails, an exception is raised.
+"""
+from .binding import (PodsError, load, library_path, pods_select, pods_advantage,
+                      grpo_token_loss_fwd_bwd, grpo_token_loss_workspace_bytes,
+                      grpo_token_loss_workspace_min_bytes, pods_last_error, PODS_F32, PODS_BF16,
+                      EXPORTED_SYMBOLS)
+
+__all__ = ["PodsError", "load", "library_path", "pods_select", "pods_advantage",
+           "grpo_token_loss_fwd_bwd", "grpo_token_loss_workspace_bytes",
+           "grpo_token_loss_workspace_min_bytes", "pods_last_error", "PODS_F32", "PODS_BF16",
+           "EXPORTED_SYMBOLS"]

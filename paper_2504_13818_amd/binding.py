@@ -1,0 +1,162 @@
+"""ctypes binding for libpods_hip.so (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpods_hip.so")
+_lib = None
+
+PODS_F32, PODS_BF16 = 0, 1
+EXPORTED_SYMBOLS = ("pods_select", "pods_advantage", "grpo_token_loss_workspace_bytes",
+                    "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
+                    "pods_last_error")
+
+_vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+
+
+class PodsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"pods status {status}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libpods_hip.so (built by paper_2504_13818_amd/build.py).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} not built: run `python -m paper_2504_13818_amd.build` "
+                                "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.pods_last_error.restype = ctypes.c_char_p
+    lib.pods_last_error.argtypes = []
+    lib.pods_select.restype = ctypes.c_int
+    lib.pods_select.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
+    lib.pods_advantage.restype = ctypes.c_int
+    lib.pods_advantage.argtypes = [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp]
+    for name in ("grpo_token_loss_workspace_bytes", "grpo_token_loss_workspace_min_bytes"):
+        f = getattr(lib, name)
+        f.restype = _sz
+        f.argtypes = [_i32, _i32, _i32, _i32, ctypes.c_int]
+    lib.grpo_token_loss_fwd_bwd.restype = ctypes.c_int
+    lib.grpo_token_loss_fwd_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
+                                            ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    _lib = lib
+    return lib
+
+
+def pods_last_error() -> str:
+    return load().pods_last_error().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise PodsError(status, pods_last_error())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _need(t, dtype, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of dtype {dtype}")
+
+
+def pods_select(rewards, m: int, sel_idx=None, sel_k=None, stream=None):
+    """rewards[B, n] float32 (device) -> (sel_idx[B, m] int32, sel_k[B] int32)."""
+    import torch
+    _need(rewards, torch.float32, "rewards")
+    B, n = rewards.shape
+    if sel_idx is None:
+        sel_idx = torch.empty((B, max(m, 0)), dtype=torch.int32, device=rewards.device)
+    if sel_k is None:
+        sel_k = torch.empty((B,), dtype=torch.int32, device=rewards.device)
+    _check(load().pods_select(_ptr(rewards), B, n, m, _ptr(sel_idx), _ptr(sel_k), _stream(stream)))
+    return sel_idx, sel_k
+
+
+def pods_advantage(rewards, sel_idx, std_eps: float = 0.0, adv=None, stream=None):
+    """rewards[B, n] float32, sel_idx[B, m] int32 (device) -> adv[B, m] float32."""
+    import torch
+    _need(rewards, torch.float32, "rewards")
+    _need(sel_idx, torch.int32, "sel_idx")
+    B, n = rewards.shape
+    m = sel_idx.shape[1]
+    if adv is None:
+        adv = torch.empty((B, m), dtype=torch.float32, device=rewards.device)
+    _check(load().pods_advantage(_ptr(rewards), _ptr(sel_idx), B, n, m, float(std_eps), _ptr(adv),
+                                 _stream(stream)))
+    return adv
+
+
+def _dt(t):
+    import torch
+    if t.dtype == torch.float32:
+        return PODS_F32
+    if t.dtype == torch.bfloat16:
+        return PODS_BF16
+    raise TypeError(f"hidden / w_lm must be float32 or bfloat16, got {t.dtype}")
+
+
+def grpo_token_loss_workspace_bytes(R, T, d, V, dt) -> int:
+    return int(load().grpo_token_loss_workspace_bytes(R, T, d, V, dt))
+
+
+def grpo_token_loss_workspace_min_bytes(R, T, d, V, dt) -> int:
+    return int(load().grpo_token_loss_workspace_min_bytes(R, T, d, V, dt))
+
+
+def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_eps: float,
+                            grad_scale: float = 1.0, workspace=None, want_logp: bool = True,
+                            out=None, stream=None):
+    """Returns dict(loss[1], logp[R, T] or None, d_hidden[R, T, d], d_w_lm[V, d]), float32 on device.
+
+    `workspace` is a uint8 CUDA tensor (allocated at the recommended size when None); `out` may
+    carry preallocated loss / logp / d_hidden / d_w_lm tensors.
+    """
+    import torch
+    dt = _dt(hidden)
+    _need(hidden, hidden.dtype, "hidden")
+    _need(w_lm, hidden.dtype, "w_lm")
+    _need(tokens, torch.int32, "tokens")
+    _need(old_logp, torch.float32, "old_logp")
+    _need(adv, torch.float32, "adv")
+    if lengths is not None:
+        _need(lengths, torch.int32, "lengths")
+    R, T, d = hidden.shape
+    V = w_lm.shape[0]
+    dev = hidden.device
+    out = dict(out or {})
+    if "loss" not in out:
+        out["loss"] = torch.empty((1,), dtype=torch.float32, device=dev)
+    if "logp" not in out:
+        out["logp"] = torch.empty((R, T), dtype=torch.float32, device=dev) if want_logp else None
+    if "d_hidden" not in out:
+        out["d_hidden"] = torch.empty((R, T, d), dtype=torch.float32, device=dev)
+    if "d_w_lm" not in out:
+        out["d_w_lm"] = torch.empty((V, d), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty((grpo_token_loss_workspace_bytes(R, T, d, V, dt),), dtype=torch.uint8,
+                                device=dev)
+    _check(load().grpo_token_loss_fwd_bwd(
+        _ptr(hidden), _ptr(w_lm), _ptr(tokens), _ptr(old_logp), _ptr(adv), _ptr(lengths), R, T, d, V,
+        dt, float(clip_eps), float(grad_scale), _ptr(out["loss"]), _ptr(out["logp"]),
+        _ptr(out["d_hidden"]), _ptr(out["d_w_lm"]), _ptr(workspace), workspace.numel(),
+        _stream(stream)))
+    out["workspace"] = workspace
+    return out

@@ -1,0 +1,90 @@
+// C ABI of the PODS HIP library: argument checks, then dispatch to the kernel families.
+#include "common.h"
+#include "loss.h"
+
+namespace pods {
+char* error_buffer() {
+    static thread_local char buf[kErrorBufferBytes] = "";
+    return buf;
+}
+}  // namespace pods
+
+using namespace pods;
+
+extern "C" {
+
+const char* pods_last_error(void) { return error_buffer(); }
+
+pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m, int32_t* sel_idx,
+                        int32_t* sel_k, void* stream) {
+    if (rewards == nullptr || sel_idx == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "pods_select: rewards and sel_idx must not be null");
+    if (B <= 0 || n <= 0 || m <= 0)
+        return fail(PODS_ERR_INVALID_ARG, "pods_select: B=%d n=%d m=%d must be positive", B, n, m);
+    if (m > n) return fail(PODS_ERR_INVALID_ARG, "pods_select: m=%d exceeds n=%d", m, n);
+    if (n > 4096) return fail(PODS_ERR_UNSUPPORTED, "pods_select: n=%d exceeds 4096", n);
+    return launch_select(rewards, B, n, m, sel_idx, sel_k, static_cast<hipStream_t>(stream));
+}
+
+pods_status pods_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
+                           int32_t m, float std_eps, float* adv, void* stream) {
+    if (rewards == nullptr || sel_idx == nullptr || adv == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "pods_advantage: null pointer");
+    if (B <= 0 || n <= 0 || m <= 0)
+        return fail(PODS_ERR_INVALID_ARG, "pods_advantage: B=%d n=%d m=%d must be positive", B, n, m);
+    if (m > n) return fail(PODS_ERR_INVALID_ARG, "pods_advantage: m=%d exceeds n=%d", m, n);
+    if (m > 4096) return fail(PODS_ERR_UNSUPPORTED, "pods_advantage: m=%d exceeds 4096", m);
+    if (!(std_eps >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "pods_advantage: std_eps < 0");
+    return launch_advantage(rewards, sel_idx, B, n, m, std_eps, adv, static_cast<hipStream_t>(stream));
+}
+
+static bool loss_sizes_ok(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt) {
+    return R > 0 && T > 0 && d > 0 && V > 0 && (dt == PODS_F32 || dt == PODS_BF16) &&
+           (int64_t)R * T <= (int64_t)1 << 30;
+}
+
+size_t grpo_token_loss_workspace_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt) {
+    if (!loss_sizes_ok(R, T, d, V, dt)) return 0;
+    return plan_loss(R, T, d, V, dt, 0).total;
+}
+
+size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt) {
+    if (!loss_sizes_ok(R, T, d, V, dt)) return 0;
+    return plan_loss(R, T, d, V, dt, 1).total;
+}
+
+pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                    const float* old_logp, const float* adv, const int32_t* lengths,
+                                    int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
+                                    float clip_eps, float grad_scale, float* loss, float* logp_out,
+                                    float* d_hidden, float* d_w_lm, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    if (hidden == nullptr || w_lm == nullptr || tokens == nullptr || old_logp == nullptr ||
+        adv == nullptr || loss == nullptr || d_hidden == nullptr || d_w_lm == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: null pointer");
+    if (R <= 0 || T <= 0 || d <= 0 || V <= 0)
+        return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: R=%d T=%d d=%d V=%d must be positive",
+                    R, T, d, V);
+    if (dt != PODS_F32 && dt != PODS_BF16)
+        return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: unknown dtype %d", (int)dt);
+    if (!(clip_eps >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: clip_eps < 0");
+    if (!(grad_scale == grad_scale)) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: grad_scale is NaN");
+    if (!loss_sizes_ok(R, T, d, V, dt))
+        return fail(PODS_ERR_UNSUPPORTED, "grpo_token_loss_fwd_bwd: R*T exceeds 2^30 positions");
+    if (d > 16384) return fail(PODS_ERR_UNSUPPORTED, "grpo_token_loss_fwd_bwd: d=%d exceeds 16384", d);
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return fail(PODS_ERR_WORKSPACE, "grpo_token_loss_fwd_bwd: workspace null or not 256-byte aligned");
+    const size_t need = plan_loss(R, T, d, V, dt, 1).total;
+    if (workspace_bytes < need)
+        return fail(PODS_ERR_WORKSPACE, "grpo_token_loss_fwd_bwd: workspace %zu B < required %zu B",
+                    workspace_bytes, need);
+    LossArgs a;
+    a.hidden = hidden; a.w_lm = w_lm; a.tokens = tokens; a.old_logp = old_logp; a.adv = adv;
+    a.lengths = lengths; a.R = R; a.T = T; a.d = d; a.V = V; a.dt = dt; a.clip_eps = clip_eps;
+    a.grad_scale = grad_scale; a.loss = loss; a.logp_out = logp_out; a.d_hidden = d_hidden;
+    a.d_w_lm = d_w_lm; a.workspace = static_cast<unsigned char*>(workspace);
+    a.workspace_bytes = workspace_bytes; a.stream = static_cast<hipStream_t>(stream);
+    return run_loss(a);
+}
+
+}  // extern "C"

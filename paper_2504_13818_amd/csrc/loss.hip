@@ -1,0 +1,264 @@
+// GRPO-PODS token loss: workspace plan, row compaction, the surrogate (clipped importance-ratio)
+// step and the loss reduction.  The two contraction-heavy parts (log-sum-exp over the vocabulary,
+// and the gradients) live in loss_simple.hip and loss_mfma.hip.
+#include "loss.h"
+
+namespace pods {
+
+LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, size_t mode) {
+    LossPlan p{};
+    p.ncap = (int64_t)R * T;
+    p.ncap_ld = (p.ncap + kTile - 1) / kTile * kTile;
+    p.mfma = (dt == PODS_BF16) && (d % 64 == 0);
+    p.slots = p.mfma ? kFwdSlotsMfma : 1;
+    p.loss_blocks = (int)ceil_div(p.ncap, 256);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    p.off_hdr = take(sizeof(LossHeader));
+    p.off_offsets = take(sizeof(int32_t) * ((size_t)R + 1));
+    p.off_rowmap = take(sizeof(int32_t) * (size_t)p.ncap_ld);
+    p.off_tok = take(sizeof(int32_t) * (size_t)p.ncap_ld);
+    p.off_lse = take(sizeof(float) * (size_t)p.ncap_ld);
+    p.off_zy = take(sizeof(float) * (size_t)p.ncap_ld);
+    p.off_g = take(sizeof(float) * (size_t)p.ncap_ld);
+    p.off_coef = take(sizeof(float) * (size_t)p.ncap_ld);
+    p.off_pmax = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
+    p.off_psum = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
+    p.off_losspart = take(sizeof(double) * (size_t)p.loss_blocks);
+    if (!p.mfma) {
+        p.vc = 0; p.nchunks = 0; p.vld = 0;
+        p.off_wt = p.off_ht = p.off_dz = p.off_dzt = off;
+        p.total = off;
+        return p;
+    }
+    const int64_t vround = ((int64_t)V + kTile - 1) / kTile * kTile;
+    // Fixed part: transposed weight (needs vld, at most vround + vc) and transposed packed hidden.
+    auto total_for = [&](int vc, LossPlan& q) {
+        size_t o = off;
+        auto tk = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+        q.vc = vc;
+        q.nchunks = (int)ceil_div(vround, vc);
+        q.vld = (int64_t)q.nchunks * vc;
+        q.off_wt = tk(2 * (size_t)d * (size_t)q.vld);
+        q.off_ht = tk(2 * (size_t)d * (size_t)p.ncap_ld);
+        q.off_dz = tk(2 * (size_t)p.ncap_ld * (size_t)vc);
+        q.off_dzt = tk(2 * (size_t)vc * (size_t)p.ncap_ld);
+        q.total = o;
+    };
+    int vc;
+    if (mode == 0) {
+        vc = (int)(vround < kDefaultVocabChunk ? vround : kDefaultVocabChunk);
+    } else if (mode == 1) {
+        vc = kTile;
+    } else {
+        vc = kTile;
+        LossPlan q = p;
+        // largest multiple of kTile (at most the whole rounded vocabulary) that fits in `mode` bytes
+        int lo = 1, hi = (int)(vround / kTile);
+        while (lo < hi) {
+            int mid = (lo + hi + 1) / 2;
+            total_for(mid * kTile, q);
+            if (q.total <= mode) lo = mid; else hi = mid - 1;
+        }
+        vc = lo * kTile;
+        if (vc > 4 * kDefaultVocabChunk) vc = 4 * kDefaultVocabChunk;
+    }
+    total_for(vc, p);
+    return p;
+}
+
+namespace {
+
+// Exclusive prefix sum of the rollout lengths: offsets[i] = first packed row of rollout i.
+__global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t* __restrict__ lengths,
+                                                            int R, int T,
+                                                            int32_t* __restrict__ offsets,
+                                                            LossHeader* __restrict__ hdr) {
+    __shared__ int32_t wave_tot[16];
+    __shared__ int32_t carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < R; base += 1024) {
+        const int i = base + tid;
+        int32_t len = 0;
+        if (i < R) len = lengths ? lengths[i] : T;
+        int32_t x = len;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int32_t t = __shfl_up(x, off, 64);
+            if (lane >= off) x += t;
+        }
+        if (lane == 63) wave_tot[wave] = x;
+        __syncthreads();
+        int32_t before = carry;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        if (i < R) offsets[i] = before + x - len;
+        __syncthreads();
+        if (tid == 1023) carry = before + x;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        offsets[R] = carry;
+        hdr->n_valid = carry;
+        hdr->gmax_bits = 0u;
+    }
+}
+
+// Packed row -> flat position map and packed token ids; clears logp_out at padded positions.
+__global__ __launch_bounds__(256) void fill_rows_kernel(const int32_t* __restrict__ lengths,
+                                                        const int32_t* __restrict__ tokens,
+                                                        const int32_t* __restrict__ offsets, int T,
+                                                        int32_t* __restrict__ row_map,
+                                                        int32_t* __restrict__ tok,
+                                                        float* __restrict__ logp_out) {
+    const int i = blockIdx.y;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    const int len = lengths ? lengths[i] : T;
+    const int64_t flat = (int64_t)i * T + t;
+    if (t < len) {
+        const int p = offsets[i] + t;
+        row_map[p] = (int32_t)flat;
+        tok[p] = tokens[flat];
+    } else if (logp_out != nullptr) {
+        logp_out[flat] = 0.0f;
+    }
+}
+
+// d_hidden rows of padded positions are zero.
+__global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __restrict__ lengths,
+                                                            int T, int d,
+                                                            float* __restrict__ d_hidden) {
+    const int64_t flat = blockIdx.x;
+    const int i = (int)(flat / T), t = (int)(flat % T);
+    if (t < lengths[i]) return;
+    float* row = d_hidden + flat * d;
+    if ((d & 3) == 0) {
+        float4* r4 = reinterpret_cast<float4*>(row);
+        for (int k = threadIdx.x; k < d / 4; k += 256) r4[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+        for (int k = threadIdx.x; k < d; k += 256) row[k] = 0.0f;
+    }
+}
+
+// Per valid token: combine the forward partials into log-sum-exp, then the surrogate of
+// Sec. 3.2: rho = exp(logp - old_logp), min[rho a, clip(rho, 1-eps, 1+eps) a], its weight
+// 1/(R len_i), and g = d loss / d logp.  Block partial sums of the loss in double.
+__global__ __launch_bounds__(256) void surrogate_kernel(
+    LossHeader* __restrict__ hdr, const int32_t* __restrict__ row_map,
+    const float* __restrict__ pmax, const float* __restrict__ psum, int slots, int64_t slot_stride,
+    const float* __restrict__ zy, const float* __restrict__ old_logp, const float* __restrict__ adv,
+    const int32_t* __restrict__ lengths, int R, int T, float clip_eps, float grad_scale,
+    float* __restrict__ lse_out, float* __restrict__ g_out, float* __restrict__ coef_out,
+    float* __restrict__ logp_out, double* __restrict__ loss_part) {
+    __shared__ double red[4];
+    __shared__ float redg[4];
+    const int n_valid = hdr->n_valid;
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    double contrib = 0.0;
+    float gabs = 0.0f;
+    if (p < n_valid) {
+        float M = -__builtin_huge_valf();
+        for (int s = 0; s < slots; ++s) M = fmaxf(M, pmax[s * slot_stride + p]);
+        float L = 0.0f;
+        for (int s = 0; s < slots; ++s) {
+            const float ms = pmax[s * slot_stride + p];
+            if (ms > -__builtin_huge_valf()) L += psum[s * slot_stride + p] * expf(ms - M);
+        }
+        const float lse = M + logf(L);
+        const int flat = row_map[p];
+        const int i = flat / T;
+        const int len = lengths ? lengths[i] : T;
+        const float a = adv[i];
+        const float c = 1.0f / ((float)R * (float)len);
+        const float logp = zy[p] - lse;
+        const float rho = expf(logp - old_logp[flat]);
+        const float lo = 1.0f - clip_eps, hi = 1.0f + clip_eps;
+        const float obj = fminf(rho * a, fminf(fmaxf(rho, lo), hi) * a);
+        const bool inactive = (a > 0.0f && rho > hi) || (a < 0.0f && rho < lo);
+        const float gp = inactive ? 0.0f : -c * a * rho * grad_scale;
+        lse_out[p] = lse;
+        g_out[p] = gp;
+        coef_out[p] = gp * -expm1f(logp);  // d loss / d z_y = g (1 - softmax_y)
+        gabs = fabsf(gp);
+        if (logp_out != nullptr) logp_out[flat] = logp;
+        contrib = -(double)c * (double)obj;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        contrib += __shfl_xor(contrib, off, 64);
+        gabs = fmaxf(gabs, __shfl_xor(gabs, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = contrib; redg[threadIdx.x >> 6] = gabs; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        loss_part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+        const float gm = fmaxf(fmaxf(redg[0], redg[1]), fmaxf(redg[2], redg[3]));
+        if (gm > 0.0f) atomicMax(&hdr->gmax_bits, __float_as_uint(gm));  // a max: order-independent
+    }
+}
+
+__global__ __launch_bounds__(1024) void finalize_loss_kernel(const double* __restrict__ loss_part,
+                                                             int nblocks, float* __restrict__ loss) {
+    __shared__ double red[1024];
+    double acc = 0.0;
+    for (int b = threadIdx.x; b < nblocks; b += 1024) acc += loss_part[b];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 512; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) loss[0] = (float)red[0];
+}
+
+}  // namespace
+
+pods_status run_loss(const LossArgs& a) {
+    const LossPlan p = plan_loss(a.R, a.T, a.d, a.V, a.dt, a.workspace_bytes);
+    unsigned char* ws = a.workspace;
+    auto* hdr = reinterpret_cast<LossHeader*>(ws + p.off_hdr);
+    auto* offsets = reinterpret_cast<int32_t*>(ws + p.off_offsets);
+    auto* row_map = reinterpret_cast<int32_t*>(ws + p.off_rowmap);
+    auto* tok = reinterpret_cast<int32_t*>(ws + p.off_tok);
+    auto* lse = reinterpret_cast<float*>(ws + p.off_lse);
+    auto* zy = reinterpret_cast<float*>(ws + p.off_zy);
+    auto* g = reinterpret_cast<float*>(ws + p.off_g);
+    auto* coef = reinterpret_cast<float*>(ws + p.off_coef);
+    auto* pmax = reinterpret_cast<float*>(ws + p.off_pmax);
+    auto* psum = reinterpret_cast<float*>(ws + p.off_psum);
+    auto* loss_part = reinterpret_cast<double*>(ws + p.off_losspart);
+    pods_status st;
+
+    hipLaunchKernelGGL(scan_lengths_kernel, dim3(1), dim3(1024), 0, a.stream, a.lengths, a.R, a.T,
+                       offsets, hdr);
+    if ((st = check_launch("scan_lengths")) != PODS_OK) return st;
+    hipLaunchKernelGGL(fill_rows_kernel, dim3((unsigned)ceil_div(a.T, 256), (unsigned)a.R), dim3(256),
+                       0, a.stream, a.lengths, a.tokens, offsets, a.T, row_map, tok, a.logp_out);
+    if ((st = check_launch("fill_rows")) != PODS_OK) return st;
+    if (a.lengths != nullptr) {
+        hipLaunchKernelGGL(zero_pad_rows_kernel, dim3((unsigned)p.ncap), dim3(256), 0, a.stream,
+                           a.lengths, a.T, a.d, a.d_hidden);
+        if ((st = check_launch("zero_pad_rows")) != PODS_OK) return st;
+    }
+
+    st = p.mfma ? mfma_forward(a, p) : simple_forward(a, p);
+    if (st != PODS_OK) return st;
+
+    hipLaunchKernelGGL(surrogate_kernel, dim3((unsigned)p.loss_blocks), dim3(256), 0, a.stream, hdr,
+                       row_map, pmax, psum, p.slots, p.ncap_ld, zy, a.old_logp, a.adv, a.lengths, a.R,
+                       a.T, a.clip_eps, a.grad_scale, lse, g, coef, a.logp_out, loss_part);
+    if ((st = check_launch("surrogate")) != PODS_OK) return st;
+    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(1024), 0, a.stream, loss_part,
+                       p.loss_blocks, a.loss);
+    if ((st = check_launch("finalize_loss")) != PODS_OK) return st;
+
+    return p.mfma ? mfma_backward(a, p) : simple_backward(a, p);
+}
+
+}  // namespace pods

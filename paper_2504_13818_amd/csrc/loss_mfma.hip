@@ -1,0 +1,670 @@
+// Matrix-core kernels for the GRPO-PODS token loss with bf16 inputs (gfx950).
+//
+// All four contractions of the update are "NT" products C[i][j] = sum_k A[i][k] B[j][k] with both
+// operands contiguous along k, computed by one workgroup per 256x256 output tile with
+// v_mfma_f32_32x32x16_bf16 and fp32 accumulators:
+//
+//   forward    z[v][t]  = sum_k W[v][k]  H[t][k]        -> running (max, sum exp) per token, z_y
+//   recompute  z[v][t]  (same)                          -> q = -2^14 exp(z - lse) as fp16 (0 at v = y),
+//                                                          stored token-major and vocab-major
+//   d_hidden   dH[k][t] = sum_v Wt[k][v] q[t][v]        -> times g_t, accumulated over vocab chunks
+//   d_w_lm     dW[k][v] = sum_t Ht[k][t] qT[v][t]       -> complete per vocabulary chunk
+//
+// The per-logit gradient is dz = g_t q / 2^14 for v != y.  q is kept in fp16 (11-bit significand)
+// rather than bf16 (8-bit) so that a logit with a large probability does not carry a 2^-8 error
+// into its token's gradient.  The token weight g_t, which spans many binades, never enters q:
+// d_hidden applies it per output row, and d_w_lm folds it into Ht = fp16(g_t h_t 2^-e) with one
+// global power-of-two range scale.  Wt = fp16(256 W) is an exact copy of the bf16 weight.
+// The generated token's own logit, dz_y = g (1 - softmax_y), dominates each token's gradient and
+// is kept out of the rounded operands altogether: its two rank-one terms, dz_y W_y into d_hidden
+// and dz_y h_t into row y of d_w_lm, are added in fp32 by two small kernels (exact bf16 products,
+// fixed summation order, no atomics).
+// (Wt, Ht are transposes made once per call so that every product is NT.)  The first
+// operand ("A role") indexes accumulator rows: a lane of the 32x32 MFMA result holds one column j
+// and rows 8b + 4(lane/32) + c, so the reduction over the vocabulary in the forward pass is
+// almost entirely inside a lane, and the gradient tiles store four consecutive k per lane.
+//
+// Workgroup: 256 threads = 4 waves as 2x2, each wave a 128x128 sub-tile (4x4 MFMA blocks, 256
+// accumulator registers).  K is walked in tiles of 64 through a double-buffered LDS stage of
+// 2 x (256 + 256) rows x 128 B; 16-byte granules within a row are XOR-swizzled by (row & 7) so
+// that the ds_read_b128 fragment loads are conflict-free.  Workgroup ids are mapped to tiles so
+// that the 32 workgroups resident on one XCD (one L2) form a 4 x 8 block of tiles and share
+// operand rows.
+#include "loss.h"
+
+namespace pods {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBK = 64;                            // k per LDS stage
+constexpr int kOperandBytes = kTile * kBK * 2;     // 32 KiB: 256 rows x 128 B
+constexpr int kStageBytes = 2 * kOperandBytes;     // A then B
+constexpr int kLdsBytes = 2 * kStageBytes;         // double buffer: 128 KiB
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kXcds = 8;
+constexpr int kSuper0 = 4, kSuper1 = 8;            // tiles per XCD block along the two tile axes
+
+struct Operand {  // this thread's 8 row pointers (bytes) into one 256-row operand tile
+    const unsigned char* ptr[8];
+};
+
+// Rows row0 + tid/8 + 32 i, granule tid%8; rows at or beyond `rows` are clamped to the last row
+// (their products are masked or multiplied by zeros by the caller).
+__device__ __forceinline__ void operand_rows(Operand& op, const uint16_t* base, int64_t ld,
+                                             int64_t row0, int64_t rows, int64_t col0,
+                                             const int32_t* __restrict__ gather) {
+    const int r = threadIdx.x >> 3, gc = threadIdx.x & 7;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int64_t row = row0 + r + 32 * i;
+        if (row >= rows) row = rows - 1;
+        if (gather != nullptr) row = gather[row];
+        op.ptr[i] = reinterpret_cast<const unsigned char*>(base + row * ld + col0 + gc * 8);
+    }
+}
+
+__device__ __forceinline__ void load_operand(const Operand& op, u32x4 (&stg)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) stg[i] = *reinterpret_cast<const u32x4*>(op.ptr[i]);
+}
+__device__ __forceinline__ void advance(Operand& op, int64_t bytes) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) op.ptr[i] += bytes;
+}
+__device__ __forceinline__ void store_operand(unsigned char* lds_operand, int wr_off,
+                                              const u32x4 (&stg)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        *reinterpret_cast<u32x4*>(lds_operand + wr_off + i * 4096) = stg[i];
+}
+
+struct LaneGeom {
+    int wr_off;   // LDS byte offset of this thread's granule in row tid/8 (+ i*4096 per row group)
+    int a_rd;     // LDS byte offset of this lane's A-role fragment row (wave's first block)
+    int b_rd;     // same for the B role
+    int cx16;     // swizzle term of the fragment granule
+    int wm, wn;   // wave position in the 2x2 wave grid
+    int lane;
+};
+
+__device__ __forceinline__ LaneGeom lane_geom() {
+    LaneGeom g;
+    const int tid = threadIdx.x;
+    g.lane = tid & 63;
+    const int wave = tid >> 6;
+    g.wm = wave >> 1;
+    g.wn = wave & 1;
+    const int r = tid >> 3, gc = tid & 7;
+    g.wr_off = r * 128 + ((gc ^ (r & 7)) << 4);
+    g.a_rd = (g.wm * 128 + (g.lane & 31)) * 128;
+    g.b_rd = (g.wn * 128 + (g.lane & 31)) * 128;
+    g.cx16 = ((g.lane >> 5) ^ (g.lane & 7)) << 4;
+    return g;
+}
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma(f16x8 a, f16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+// One LDS stage (k = 64): four k-steps of 4 + 4 fragment loads and 16 MFMAs.  E is the operand
+// element vector type (bf16x8 for the logits, f16x8 for the gradient contractions).
+template <typename E>
+__device__ __forceinline__ void mma_stage(const unsigned char* stage, const LaneGeom& g,
+                                          f32x16 (&acc)[4][4]) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        const int ko = (ks * 32) ^ g.cx16;
+        E af[4], bfr[4];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+            af[mi] = *reinterpret_cast<const E*>(stage + g.a_rd + mi * 4096 + ko);
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+            bfr[ni] = *reinterpret_cast<const E*>(stage + kOperandBytes + g.b_rd + ni * 4096 + ko);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma(af[mi], bfr[ni], acc[mi][ni]);
+    }
+}
+
+// acc += A[256 x (64 KT)] . B[256 x (64 KT)]^T.  On return both operands have advanced 128 KT bytes
+// and every wave has left the LDS stage.
+template <typename E>
+__device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned char* lds,
+                                       const LaneGeom& g, f32x16 (&acc)[4][4]) {
+    u32x4 sa[8], sb[8];
+    load_operand(A, sa);
+    load_operand(B, sb);
+    advance(A, 128);
+    advance(B, 128);
+    store_operand(lds, g.wr_off, sa);
+    store_operand(lds + kOperandBytes, g.wr_off, sb);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        unsigned char* cur = lds + (kt & 1) * kStageBytes;
+        unsigned char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
+        const bool more = kt + 1 < KT;
+        if (more) {
+            load_operand(A, sa);
+            load_operand(B, sb);
+            advance(A, 128);
+            advance(B, 128);
+        }
+        mma_stage<E>(cur, g, acc);
+        if (more) {
+            store_operand(nxt, g.wr_off, sa);
+            store_operand(nxt + kOperandBytes, g.wr_off, sb);
+        }
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
+}
+
+// Workgroup id -> tile (t0, t1) of an n0 x n1 tile grid, so that ids congruent mod 8 (one XCD)
+// walk 4 x 8 blocks of tiles.  Returns false for ids that fall outside the grid.
+__host__ __device__ inline int64_t super_grid_blocks(int64_t n0, int64_t n1) {
+    const int64_t nst = ((n0 + kSuper0 - 1) / kSuper0) * ((n1 + kSuper1 - 1) / kSuper1);
+    return (nst + kXcds - 1) / kXcds * kXcds * (kSuper0 * kSuper1);
+}
+__device__ __forceinline__ bool decode_tile(int64_t bid, int64_t n0, int64_t n1, int64_t& t0, int64_t& t1) {
+    const int64_t nst1 = (n1 + kSuper1 - 1) / kSuper1;
+    const int64_t xcd = bid % kXcds, q = bid / kXcds;
+    const int64_t st = (q / (kSuper0 * kSuper1)) * kXcds + xcd;
+    const int w = (int)(q % (kSuper0 * kSuper1));
+    t0 = (st / nst1) * kSuper0 + w / kSuper1;
+    t1 = (st % nst1) * kSuper1 + w % kSuper1;
+    return t0 < n0 && t1 < n1;
+}
+
+// Accumulator element (mi, r) of a lane sits at row mi*32 + 8*(r/4) + 4*(lane/32) + r%4 of the
+// wave's 128-row sub-tile.  Inverse for one row offset `rel` (relative to the sub-tile, already
+// reduced by 4*(lane/32)): register index mi*16 + r, or -1 if this lane does not hold it.
+__device__ __forceinline__ int acc_slot_of(int rel) {
+    if (rel < 0 || rel >= 128 || (rel & 4) != 0) return -1;
+    return ((rel >> 5) << 4) | (((rel >> 3) & 3) << 2) | (rel & 3);
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward: per token, (max, sum exp) over this workgroup's share of the vocabulary, and z_y.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restrict__ hdr,
+                                                     const int32_t* __restrict__ row_map,
+                                                     const int32_t* __restrict__ tok,
+                                                     const uint16_t* __restrict__ hidden,
+                                                     const uint16_t* __restrict__ w, int d, int V,
+                                                     int64_t slot_stride, float* __restrict__ pmax,
+                                                     float* __restrict__ psum, float* __restrict__ zy) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int n_valid = hdr->n_valid;
+    // ids congruent mod 8 (one XCD): 4 token tiles x 8 vocabulary splits
+    const int64_t bid = blockIdx.x;
+    const int64_t xcd = bid % kXcds, q = bid / kXcds;
+    const int64_t tt = ((q / 32) * kXcds + xcd) * 4 + (q % 32) / kFwdVocabSplits;
+    const int vs = (int)(q % kFwdVocabSplits);
+    if (tt * kTile >= n_valid) return;
+    const LaneGeom g = lane_geom();
+    const int nvt = (V + kTile - 1) / kTile;
+    const int KT = d / kBK;
+
+    Operand A, B;
+    operand_rows(B, hidden, d, tt * kTile, n_valid, 0, row_map);
+
+    int y[4];
+    float M[4], L[4];
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+        y[ni] = (p < n_valid) ? tok[p] : -1;
+        M[ni] = -__builtin_huge_valf();
+        L[ni] = 0.0f;
+    }
+
+    f32x16 acc[4][4];
+    for (int vt = vs; vt < nvt; vt += kFwdVocabSplits) {
+        zero_acc(acc);
+        operand_rows(A, w, d, (int64_t)vt * kTile, V, 0, nullptr);
+        k_loop<bf16x8>(A, B, KT, lds, g, acc);
+        advance(B, -(int64_t)KT * 128);
+
+        const int vbase = vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // row of (mi=0, r=0)
+        if (vt * kTile + kTile > V) {  // last, partial vocabulary tile: rows >= V do not exist
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int v = vbase + mi * 32 + 8 * (r >> 2) + (r & 3);
+                    if (v >= V) {
+#pragma unroll
+                        for (int ni = 0; ni < 4; ++ni) acc[mi][ni][r] = -__builtin_huge_valf();
+                    }
+                }
+        }
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            // z_y lives in exactly one lane of one wave of one vocabulary tile
+            const int slot = acc_slot_of(y[ni] - vbase);
+            if (__any(slot >= 0)) {
+                float val = 0.0f;
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (slot == mi * 16 + r) val = acc[mi][ni][r];
+                if (slot >= 0) zy[tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31)] = val;
+            }
+            float m = acc[0][ni][0];
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[mi][ni][r]);
+            const float Mn = fmaxf(M[ni], m);
+            const float Ms = (Mn == -__builtin_huge_valf()) ? 0.0f : Mn;
+            const float off = -Ms * kLog2e;
+            float s = 0.0f;
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    s += __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e, off));
+            L[ni] = L[ni] * __builtin_amdgcn_exp2f(fmaf(M[ni], kLog2e, off)) + s;
+            M[ni] = Mn;
+        }
+    }
+
+    // lanes l and l^32 hold the same tokens over different vocabulary rows
+    const int slot_id = vs * 2 + g.wm;
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        const float Mo = __shfl_xor(M[ni], 32, 64);
+        const float Lo = __shfl_xor(L[ni], 32, 64);
+        const float Mn = fmaxf(M[ni], Mo);
+        float Lt = 0.0f;
+        if (Mn > -__builtin_huge_valf()) {
+            Lt = L[ni] * __builtin_amdgcn_exp2f((M[ni] - Mn) * kLog2e) +
+                 Lo * __builtin_amdgcn_exp2f((Mo - Mn) * kLog2e);
+        }
+        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+        if (g.lane < 32 && p < n_valid) {
+            pmax[slot_id * slot_stride + p] = Mn;
+            psum[slot_id * slot_stride + p] = Lt;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward step 1 (per vocabulary chunk): recompute the logits tile and form
+// q = -kQScale exp(z - lse), rounded to fp16, 0 at v = y, in both layouts (dz = g q / kQScale).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 1) void recompute_kernel(
+    const LossHeader* __restrict__ hdr, const int32_t* __restrict__ row_map,
+    const int32_t* __restrict__ tok, const float* __restrict__ lse,
+    const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int d, int V, int v0,
+    int vc, int64_t ncap_ld, _Float16* __restrict__ q, _Float16* __restrict__ qt) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int n_valid = hdr->n_valid;
+    const int64_t ntt = (n_valid + kTile - 1) / kTile;
+    int64_t tt, vt;
+    if (!decode_tile(blockIdx.x, ntt, vc / kTile, tt, vt)) return;
+    const LaneGeom g = lane_geom();
+    const int KT = d / kBK;
+
+    Operand A, B;
+    operand_rows(A, w, d, (int64_t)v0 + vt * kTile, V, 0, nullptr);
+    operand_rows(B, hidden, d, tt * kTile, n_valid, 0, row_map);
+    f32x16 acc[4][4];
+    zero_acc(acc);
+    k_loop<bf16x8>(A, B, KT, lds, g, acc);
+
+    const int vloc = (int)vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // chunk-local row of (mi=0, r=0)
+    const int vbase = v0 + vloc;
+    const bool partial = (v0 + (int)vt * kTile + kTile > V);
+    constexpr float kLog2Q = 14.0f;
+    static_assert(kQScale == 16384.0f, "kLog2Q must be log2(kQScale)");
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+        const bool valid = p < n_valid;
+        const int y = valid ? tok[p] : -1;
+        // kQScale softmax = 2^(z log2e - lse log2e + 14); rows past N get 2^-inf = 0
+        const float off = valid ? fmaf(-lse[p], kLog2e, kLog2Q) : -__builtin_huge_valf();
+        float val[4][16];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                val[mi][r] = -__builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e, off));
+        const int slot = acc_slot_of(y - vbase);
+        if (__any(slot >= 0)) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (slot == mi * 16 + r) val[mi][r] = 0.0f;  // the y logit is handled in fp32
+        }
+        if (partial) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (vbase + mi * 32 + 8 * (r >> 2) + (r & 3) >= V) val[mi][r] = 0.0f;
+        }
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                f16x4 pk;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) pk[c] = (_Float16)val[mi][b * 4 + c];
+                const int vl = vloc + mi * 32 + 8 * b;
+                *reinterpret_cast<f16x4*>(q + p * vc + vl) = pk;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) qt[(int64_t)(vl + c) * ncap_ld + p] = pk[c];
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward step 2: d_hidden[t][k] += (g_t / (kQScale kWScale)) sum_{v in chunk} q[t][v] Wt[k][v]
+// (the rows were initialised with the y-logit term)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict__ hdr,
+                                                    const int32_t* __restrict__ row_map,
+                                                    const float* __restrict__ gvec,
+                                                    const uint16_t* __restrict__ wt, int64_t vld,
+                                                    const uint16_t* __restrict__ q, int d, int v0,
+                                                    int vc, float* __restrict__ d_hidden) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int n_valid = hdr->n_valid;
+    const int64_t ntt = (n_valid + kTile - 1) / kTile;
+    int64_t tt, kt0;
+    if (!decode_tile(blockIdx.x, ntt, (d + kTile - 1) / kTile, tt, kt0)) return;
+    const LaneGeom g = lane_geom();
+
+    Operand A, B;
+    operand_rows(A, wt, vld, kt0 * kTile, d, v0, nullptr);
+    // every row of the last token tile was written by the recompute step (zeros past N)
+    operand_rows(B, q, vc, tt * kTile, ntt * kTile, 0, nullptr);
+    f32x16 acc[4][4];
+    zero_acc(acc);
+    k_loop<f16x8>(A, B, vc / kBK, lds, g, acc);
+
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+        if (p >= n_valid) continue;
+        const float scale = gvec[p] * (1.0f / (kQScale * kWScale));
+        float* row = d_hidden + (int64_t)row_map[p] * d;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int k = (int)kt0 * kTile + g.wm * 128 + mi * 32 + 8 * b + 4 * (g.lane >> 5);
+                if (k >= d) continue;
+                f32x4 v;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] = acc[mi][ni][b * 4 + c] * scale;
+                f32x4* dst = reinterpret_cast<f32x4*>(row + k);
+                *dst = v + *dst;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward step 3: d_w_lm[v][k] = (1 / (kQScale s)) sum_t qT[v][t] Ht[k][t], Ht = g_t h_t s
+// (all tokens: complete per chunk)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict__ hdr,
+                                                    const uint16_t* __restrict__ ht,
+                                                    const uint16_t* __restrict__ qt,
+                                                    int64_t ncap_ld, int d, int V, int v0, int vc,
+                                                    float* __restrict__ d_w) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int n_valid = hdr->n_valid;
+    int64_t vt, kt0;
+    if (!decode_tile(blockIdx.x, vc / kTile, (d + kTile - 1) / kTile, vt, kt0)) return;
+    if ((int64_t)v0 + vt * kTile >= V) return;
+    const LaneGeom g = lane_geom();
+
+    Operand A, B;
+    operand_rows(A, ht, ncap_ld, kt0 * kTile, d, 0, nullptr);
+    operand_rows(B, qt, ncap_ld, vt * kTile, vc, 0, nullptr);
+    f32x16 acc[4][4];
+    zero_acc(acc);
+    const int KT = (n_valid + kBK - 1) / kBK;
+    if (KT > 0) k_loop<f16x8>(A, B, KT, lds, g, acc);
+    const float scale = 1.0f / (kQScale * g_range_scale(hdr));
+
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        const int64_t v = (int64_t)v0 + vt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+        if (v >= V) continue;
+        float* row = d_w + v * d;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int k = (int)kt0 * kTile + g.wm * 128 + mi * 32 + 8 * b + 4 * (g.lane >> 5);
+                if (k >= d) continue;
+                f32x4 vv;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) vv[c] = acc[mi][ni][b * 4 + c] * scale;
+                *reinterpret_cast<f32x4*>(row + k) = vv;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// The generated token's own logit, in fp32.  coef_t = g_t (1 - softmax_y) = d loss / d z_y.
+//   d_hidden[t][:]  = coef_t W[y_t][:]            (initialises the row; the chunks accumulate on it)
+//   d_w_lm[y_t][:] += coef_t h_t[:]               (after the chunks have stored their rows)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dh_onehot_kernel(const LossHeader* __restrict__ hdr,
+                                                        const int32_t* __restrict__ row_map,
+                                                        const int32_t* __restrict__ tok,
+                                                        const float* __restrict__ coef,
+                                                        const uint16_t* __restrict__ w, int d,
+                                                        float* __restrict__ d_hidden) {
+    const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // one wave per token
+    if (p >= hdr->n_valid) return;
+    const int lane = threadIdx.x & 63;
+    const float c = coef[p];
+    const uint16_t* wrow = w + (int64_t)tok[p] * d;
+    float* out = d_hidden + (int64_t)row_map[p] * d;
+    for (int k = lane * 8; k < d; k += 512) {   // d % 64 == 0: whole groups of 8
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(wrow + k);
+        f32x4 lo, hi;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float e0 = __uint_as_float(raw[j] << 16), e1 = __uint_as_float(raw[j] & 0xFFFF0000u);
+            if (j < 2) { lo[2 * j] = c * e0; lo[2 * j + 1] = c * e1; }
+            else { hi[2 * j - 4] = c * e0; hi[2 * j - 3] = c * e1; }
+        }
+        *reinterpret_cast<f32x4*>(out + k) = lo;
+        *reinterpret_cast<f32x4*>(out + k + 4) = hi;
+    }
+}
+
+// One wave owns 64 consecutive vocabulary rows and walks every token in order; a row's terms are
+// therefore added by the same lanes in ascending token order, whatever the timing.
+constexpr int kOnehotRows = 64;
+__global__ __launch_bounds__(256) void dw_onehot_kernel(const LossHeader* __restrict__ hdr,
+                                                        const int32_t* __restrict__ row_map,
+                                                        const int32_t* __restrict__ tok,
+                                                        const float* __restrict__ coef,
+                                                        const uint16_t* __restrict__ hidden, int d,
+                                                        int V, float* __restrict__ d_w) {
+    const int n_valid = hdr->n_valid;
+    const int lane = threadIdx.x & 63;
+    const int v_lo = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kOnehotRows;
+    if (v_lo >= V) return;
+    for (int p0 = 0; p0 < n_valid; p0 += 64) {
+        const int p = p0 + lane;
+        const int y = (p < n_valid) ? tok[p] : -1;
+        unsigned long long hits = __ballot((unsigned)(y - v_lo) < (unsigned)kOnehotRows);
+        while (hits != 0ull) {
+            const int src = __ffsll((long long)hits) - 1;
+            hits &= hits - 1ull;
+            const int pp = p0 + src;
+            const int yy = __shfl(y, src, 64);
+            const float c = coef[pp];
+            if (c == 0.0f) continue;
+            const uint16_t* hrow = hidden + (int64_t)row_map[pp] * d;
+            float* out = d_w + (int64_t)yy * d;
+            for (int k = lane * 8; k < d; k += 512) {
+                const u32x4 raw = *reinterpret_cast<const u32x4*>(hrow + k);
+                f32x4 lo = *reinterpret_cast<f32x4*>(out + k);
+                f32x4 hi = *reinterpret_cast<f32x4*>(out + k + 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float e0 = __uint_as_float(raw[j] << 16), e1 = __uint_as_float(raw[j] & 0xFFFF0000u);
+                    if (j < 2) { lo[2 * j] += c * e0; lo[2 * j + 1] += c * e1; }
+                    else { hi[2 * j - 4] += c * e0; hi[2 * j - 3] += c * e1; }
+                }
+                *reinterpret_cast<f32x4*>(out + k) = lo;
+                *reinterpret_cast<f32x4*>(out + k + 4) = hi;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// fp16 transposed copies (once per call):
+//   Wt[k][v] = kWScale W[v][k]            (zero for v >= V; exact: bf16 has fewer significand bits)
+//   Ht[k][p] = s g_p H[row_map[p]][k]     (zero for p >= N up to the end of the last token tile;
+//                                          s = the global range scale of g)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_kernel(const LossHeader* __restrict__ hdr,
+                                                        const int32_t* __restrict__ gather,
+                                                        const float* __restrict__ gvec,
+                                                        const uint16_t* __restrict__ src, int64_t rows,
+                                                        int d, int64_t ld_out, int token_rows,
+                                                        _Float16* __restrict__ dst) {
+    __shared__ _Float16 tile[64][66];
+    int64_t nrows = rows;
+    int64_t fill_to = ld_out;
+    float common = kWScale;
+    if (token_rows) {
+        nrows = hdr->n_valid;
+        fill_to = (nrows + kTile - 1) / kTile * kTile;
+        common = g_range_scale(hdr);
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * 64;
+    const int k0 = blockIdx.y * 64;
+    if (r0 >= fill_to) return;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int64_t r = r0 + rr;
+        float x = 0.0f;
+        if (r < nrows && k0 + tx < d) {
+            const int64_t srow = gather ? (int64_t)gather[r] : r;
+            x = __uint_as_float((uint32_t)src[srow * d + k0 + tx] << 16) * common;
+            if (token_rows) x *= gvec[r];
+        }
+        tile[rr][tx] = (_Float16)x;
+    }
+    __syncthreads();
+    for (int kk = ty; kk < 64; kk += 4) {
+        if (k0 + kk < d && r0 + tx < ld_out) dst[(int64_t)(k0 + kk) * ld_out + r0 + tx] = tile[tx][kk];
+    }
+}
+
+pods_status reserve(const void* kernel, const char* what) {
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return fail(PODS_ERR_RUNTIME, "%s: cannot reserve LDS: %s", what, hipGetErrorString(e));
+    return PODS_OK;
+}
+
+}  // namespace
+
+pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
+    unsigned char* ws = a.workspace;
+    pods_status st = reserve(reinterpret_cast<const void*>(fwd_kernel), "token loss forward");
+    if (st != PODS_OK) return st;
+    const int64_t ntt = p.ncap_ld / kTile;
+    const int64_t groups = (ntt + 3) / 4;                                // 4 token tiles each
+    const int64_t grid = (groups + kXcds - 1) / kXcds * kXcds * 32;
+    hipLaunchKernelGGL(fwd_kernel, dim3((unsigned)grid), dim3(256), kLdsBytes, a.stream,
+                       reinterpret_cast<const LossHeader*>(ws + p.off_hdr),
+                       reinterpret_cast<const int32_t*>(ws + p.off_rowmap),
+                       reinterpret_cast<const int32_t*>(ws + p.off_tok),
+                       static_cast<const uint16_t*>(a.hidden), static_cast<const uint16_t*>(a.w_lm),
+                       a.d, a.V, p.ncap_ld, reinterpret_cast<float*>(ws + p.off_pmax),
+                       reinterpret_cast<float*>(ws + p.off_psum),
+                       reinterpret_cast<float*>(ws + p.off_zy));
+    return check_launch("token loss forward");
+}
+
+pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
+    unsigned char* ws = a.workspace;
+    auto* hdr = reinterpret_cast<const LossHeader*>(ws + p.off_hdr);
+    auto* row_map = reinterpret_cast<const int32_t*>(ws + p.off_rowmap);
+    auto* tok = reinterpret_cast<const int32_t*>(ws + p.off_tok);
+    auto* lse = reinterpret_cast<const float*>(ws + p.off_lse);
+    auto* g = reinterpret_cast<const float*>(ws + p.off_g);
+    auto* coef = reinterpret_cast<const float*>(ws + p.off_coef);
+    auto* wt = reinterpret_cast<_Float16*>(ws + p.off_wt);
+    auto* ht = reinterpret_cast<_Float16*>(ws + p.off_ht);
+    auto* dz = reinterpret_cast<_Float16*>(ws + p.off_dz);
+    auto* dzt = reinterpret_cast<_Float16*>(ws + p.off_dzt);
+    const auto* hidden = static_cast<const uint16_t*>(a.hidden);
+    const auto* w = static_cast<const uint16_t*>(a.w_lm);
+    pods_status st;
+    if ((st = reserve(reinterpret_cast<const void*>(recompute_kernel), "token loss recompute")) != PODS_OK) return st;
+    if ((st = reserve(reinterpret_cast<const void*>(dh_kernel), "token loss d_hidden")) != PODS_OK) return st;
+    if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
+
+    const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)(p.vld / 64), dtiles64), dim3(256), 0, a.stream,
+                       hdr, nullptr, nullptr, w, (int64_t)a.V, a.d, p.vld, 0, wt);
+    if ((st = check_launch("transpose W")) != PODS_OK) return st;
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
+                       a.stream, hdr, row_map, g, hidden, (int64_t)0, a.d, p.ncap_ld, 1, ht);
+    if ((st = check_launch("transpose H")) != PODS_OK) return st;
+
+    hipLaunchKernelGGL(dh_onehot_kernel, dim3((unsigned)ceil_div(p.ncap, 4)), dim3(256), 0, a.stream, hdr,
+                       row_map, tok, coef, w, a.d, a.d_hidden);
+    if ((st = check_launch("token loss d_hidden (y logit)")) != PODS_OK) return st;
+
+    const int64_t ntt = p.ncap_ld / kTile;
+    const int64_t dt256 = ceil_div(a.d, kTile);
+    const int64_t vt_chunk = p.vc / kTile;
+    for (int c = 0; c < p.nchunks; ++c) {
+        const int v0 = c * p.vc;
+        if (v0 >= a.V) break;
+        hipLaunchKernelGGL(recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
+                           kLdsBytes, a.stream, hdr, row_map, tok, lse, hidden, w, a.d, a.V, v0, p.vc,
+                           p.ncap_ld, dz, dzt);
+        if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
+        hipLaunchKernelGGL(dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
+                           a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(wt), p.vld,
+                           reinterpret_cast<const uint16_t*>(dz), a.d, v0, p.vc, a.d_hidden);
+        if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
+        hipLaunchKernelGGL(dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
+                           kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(ht),
+                           reinterpret_cast<const uint16_t*>(dzt), p.ncap_ld, a.d, a.V, v0, p.vc, a.d_w_lm);
+        if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
+    }
+    hipLaunchKernelGGL(dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,
+                       a.stream, hdr, row_map, tok, coef, hidden, a.d, a.V, a.d_w_lm);
+    return check_launch("token loss d_w_lm (y logit)");
+}
+
+}  // namespace pods

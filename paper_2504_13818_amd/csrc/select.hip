@@ -1,0 +1,247 @@
+// Max-variance down-sampling (Sec. 3.3: Lemma 3.1, Algorithm 2, Theorem 1), one prompt group
+// per wavefront.
+//
+// Each lane holds KPL consecutive elements of the group as 64-bit sort keys.  A key is the
+// order-preserving integer image of the float32 reward followed by the element's index, laid
+// into the mantissa of a double in [2, 4): for such doubles floating-point order equals integer
+// order, so a compare-exchange is one v_min_f64 and one v_max_f64.  The index in the low bits
+// makes every key distinct and gives the (reward, index) order the tie rule asks for.
+// A bitonic network sorts the 64*KPL keys in registers; the sorted rewards and indices are staged
+// in LDS; prefix sums of r and r^2 over the m lowest and running sums over the k highest are
+// scanned in double precision; one candidate split k per lane is scored as m*Q - S^2 (m^2 times
+// its variance), candidates that repeat the previous multiset are passed over, and a wave
+// arg-max (smallest k on equal scores) picks k.
+#include "common.h"
+
+namespace pods {
+namespace {
+
+constexpr int kIdxBits = 12;  // n <= 4096
+
+__device__ __forceinline__ double make_key(float r, uint32_t e) {
+    r = r + 0.0f;  // -0.0 -> +0.0
+    uint32_t b = __float_as_uint(r);
+    uint32_t ou = b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);  // unsigned order == float order
+    uint64_t k = (1ull << 62) | ((uint64_t)ou << kIdxBits) | e;
+    return __longlong_as_double((long long)k);
+}
+__device__ __forceinline__ double pad_key(uint32_t e) {
+    uint64_t k = (1ull << 62) | ((uint64_t)0xFFFFFFFFu << kIdxBits) | e;  // after every real reward
+    return __longlong_as_double((long long)k);
+}
+__device__ __forceinline__ float key_reward(double key) {
+    uint64_t k = (uint64_t)__double_as_longlong(key);
+    uint32_t ou = (uint32_t)(k >> kIdxBits);
+    uint32_t b = ou ^ ((ou >> 31) ? 0x80000000u : 0xFFFFFFFFu);
+    return __uint_as_float(b);
+}
+__device__ __forceinline__ uint32_t key_index(double key) {
+    return (uint32_t)__double_as_longlong(key) & ((1u << kIdxBits) - 1u);
+}
+
+__device__ __forceinline__ void cmp_exchange(double& lo, double& hi) {
+    double a = fmin(lo, hi), b = fmax(lo, hi);
+    lo = a;
+    hi = b;
+}
+
+// First step of a bitonic merge of blocks of `SIZE`: element e meets e ^ (SIZE-1).
+template <int KPL, int SIZE>
+__device__ __forceinline__ void stage_mirror(double (&key)[KPL], int lane) {
+    if constexpr (SIZE <= KPL) {
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+            const int p = j ^ (SIZE - 1);
+            if (j < p) cmp_exchange(key[j], key[p]);
+        }
+    } else {
+        constexpr int LM = SIZE / KPL - 1;          // lane ^ LM, register KPL-1-j
+        const bool lower = (lane & ((LM + 1) >> 1)) == 0;
+        double other[KPL];
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) other[j] = __shfl_xor(key[KPL - 1 - j], LM, kWave);
+#pragma unroll
+        for (int j = 0; j < KPL; ++j)
+            key[j] = lower ? fmin(key[j], other[j]) : fmax(key[j], other[j]);
+    }
+}
+
+// Later steps of a merge: element e meets e ^ STRIDE.
+template <int KPL, int STRIDE>
+__device__ __forceinline__ void stage_xor(double (&key)[KPL], int lane) {
+    if constexpr (STRIDE < KPL) {
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+            const int p = j ^ STRIDE;
+            if (j < p) cmp_exchange(key[j], key[p]);
+        }
+    } else {
+        constexpr int LM = STRIDE / KPL;
+        const bool lower = (lane & LM) == 0;
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+            double other = __shfl_xor(key[j], LM, kWave);
+            key[j] = lower ? fmin(key[j], other) : fmax(key[j], other);
+        }
+    }
+}
+
+template <int KPL, int SIZE, int STRIDE>
+__device__ __forceinline__ void merge_steps(double (&key)[KPL], int lane) {
+    if constexpr (STRIDE >= 1) {
+        stage_xor<KPL, STRIDE>(key, lane);
+        merge_steps<KPL, SIZE, STRIDE / 2>(key, lane);
+    }
+}
+
+template <int KPL, int SIZE>
+__device__ __forceinline__ void sort_from(double (&key)[KPL], int lane) {
+    if constexpr (SIZE <= kWave * KPL) {
+        stage_mirror<KPL, SIZE>(key, lane);
+        merge_steps<KPL, SIZE, SIZE / 4>(key, lane);
+        sort_from<KPL, SIZE * 2>(key, lane);
+    }
+}
+
+__device__ __forceinline__ double wave_inclusive_scan(double x, int lane) {
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        double t = __shfl_up(x, off, kWave);
+        if (lane >= off) x += t;
+    }
+    return x;
+}
+
+// Dynamic LDS per wave: float val[N]; uint16 idx[N]; double p1[m+1]; double p2[m+1].
+__host__ __device__ inline size_t wave_lds_bytes(int N, int m) {
+    size_t b = (size_t)N * 4 + (size_t)N * 2;
+    b = (b + 7) / 8 * 8;
+    return b + 2 * (size_t)(m + 1) * 8;
+}
+
+template <int KPL, int WAVES>
+__global__ __launch_bounds__(WAVES* kWave) void select_kernel(const float* __restrict__ rewards,
+                                                              int B, int n, int m,
+                                                              int32_t* __restrict__ sel_idx,
+                                                              int32_t* __restrict__ sel_k) {
+    constexpr int N = kWave * KPL;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int group = blockIdx.x * WAVES + wave;
+    const bool live = group < B;  // dead waves still take every barrier
+
+    unsigned char* base = lds_raw + (size_t)wave * wave_lds_bytes(N, m);
+    float* s_val = reinterpret_cast<float*>(base);
+    uint16_t* s_idx = reinterpret_cast<uint16_t*>(base + (size_t)N * 4);
+    double* p1 = reinterpret_cast<double*>(base + ((size_t)N * 6 + 7) / 8 * 8);
+    double* p2 = p1 + (m + 1);
+
+    // ---- load and key (Alg. 2 step 1 input) ----
+    double key[KPL];
+    const float* row = rewards + (size_t)(live ? group : 0) * n;
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) {
+        const int e = lane * KPL + j;
+        key[j] = (e < n) ? make_key(row[e], (uint32_t)e) : pad_key((uint32_t)e);
+    }
+
+    // ---- argsort ascending by (reward, index) ----
+    sort_from<KPL, 2>(key, lane);
+
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) {
+        const int e = lane * KPL + j;
+        s_val[e] = key_reward(key[j]);
+        s_idx[e] = (uint16_t)key_index(key[j]);
+    }
+    __syncthreads();
+
+    // ---- Theorem 1: prefix sums of r and r^2 over the m lowest ----
+    double c1 = 0.0, c2 = 0.0;
+    if (lane == 0) { p1[0] = 0.0; p2[0] = 0.0; }
+    for (int e0 = 0; e0 < m; e0 += kWave) {
+        const int e = e0 + lane;
+        const double x = (e < m) ? (double)s_val[e] : 0.0;
+        const double a1 = wave_inclusive_scan(x, lane) + c1;
+        const double a2 = wave_inclusive_scan(x * x, lane) + c2;
+        if (e < m) { p1[e + 1] = a1; p2[e + 1] = a2; }
+        c1 = __shfl(a1, kWave - 1, kWave);
+        c2 = __shfl(a2, kWave - 1, kWave);
+    }
+    __syncthreads();
+
+    // ---- Alg. 2 steps 2-6: score every split k, keep the first strict maximum ----
+    double best = -__builtin_huge_val();
+    int best_k = 0x7fffffff;
+    c1 = 0.0;
+    c2 = 0.0;
+    const double dm = (double)m;
+    for (int k0 = 0; k0 <= m; k0 += kWave) {
+        const int k = k0 + lane;
+        const bool in = (k >= 1) && (k <= m);
+        const float top = in ? s_val[n - k] : 0.0f;
+        const double x = (double)top;
+        const double u1 = wave_inclusive_scan(x, lane) + c1;   // sum of the k highest
+        const double u2 = wave_inclusive_scan(x * x, lane) + c2;
+        c1 = __shfl(u1, kWave - 1, kWave);
+        c2 = __shfl(u2, kWave - 1, kWave);
+        bool eligible = (k == 0);
+        if (in) eligible = (top != s_val[m - k]);   // else same multiset as split k-1
+        if (eligible) {
+            const double S = p1[m - k] + u1;
+            const double Q = p2[m - k] + u2;
+            const double D = dm * Q - S * S;
+            if (D > best) { best = D; best_k = k; }
+        }
+    }
+#pragma unroll
+    for (int off = kWave / 2; off >= 1; off >>= 1) {
+        const double ob = __shfl_xor(best, off, kWave);
+        const int ok = __shfl_xor(best_k, off, kWave);
+        if (ob > best || (ob == best && ok < best_k)) { best = ob; best_k = ok; }
+    }
+
+    // ---- emit the (m-k) lowest then the k highest ----
+    if (live) {
+        int32_t* out = sel_idx + (size_t)group * m;
+        for (int j = lane; j < m; j += kWave)
+            out[j] = (j < m - best_k) ? (int32_t)s_idx[j] : (int32_t)s_idx[n - m + j];
+        if (sel_k != nullptr && lane == 0) sel_k[group] = best_k;
+    }
+}
+
+template <int KPL, int WAVES>
+pods_status launch_variant(const float* rewards, int32_t B, int32_t n, int32_t m, int32_t* sel_idx,
+                           int32_t* sel_k, hipStream_t stream) {
+    const size_t lds = (size_t)WAVES * wave_lds_bytes(kWave * KPL, m);
+    if (lds > 160 * 1024) return fail(PODS_ERR_UNSUPPORTED, "pods_select: LDS need %zu B", lds);
+    auto kernel = select_kernel<KPL, WAVES>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return fail(PODS_ERR_RUNTIME, "pods_select: cannot reserve %zu B of LDS: %s", lds,
+                        hipGetErrorString(e));
+    }
+    const unsigned grid = (unsigned)ceil_div(B, WAVES);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(WAVES * kWave), lds, stream, rewards, B, n, m,
+                       sel_idx, sel_k);
+    return check_launch("pods_select");
+}
+
+}  // namespace
+
+pods_status launch_select(const float* rewards, int32_t B, int32_t n, int32_t m, int32_t* sel_idx,
+                          int32_t* sel_k, hipStream_t stream) {
+    if (n <= 64) return launch_variant<1, 4>(rewards, B, n, m, sel_idx, sel_k, stream);
+    if (n <= 128) return launch_variant<2, 4>(rewards, B, n, m, sel_idx, sel_k, stream);
+    if (n <= 256) return launch_variant<4, 4>(rewards, B, n, m, sel_idx, sel_k, stream);
+    if (n <= 512) return launch_variant<8, 2>(rewards, B, n, m, sel_idx, sel_k, stream);
+    if (n <= 1024) return launch_variant<16, 2>(rewards, B, n, m, sel_idx, sel_k, stream);
+    if (n <= 2048) return launch_variant<32, 1>(rewards, B, n, m, sel_idx, sel_k, stream);
+    if (n <= 4096) return launch_variant<64, 1>(rewards, B, n, m, sel_idx, sel_k, stream);
+    return fail(PODS_ERR_UNSUPPORTED, "pods_select: n = %d exceeds 4096", n);
+}
+
+}  // namespace pods

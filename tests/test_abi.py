@@ -1,0 +1,69 @@
+"""The C-ABI library loads on a machine without a GPU, exports every symbol include/pods.h
+declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2504_13818_amd as lib
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pods.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(pods_[a-z_]+|grpo_[a-z_]+)\s*\(", text))
+
+
+def test_every_declared_symbol_is_exported():
+    l = lib.load()
+    declared = _declared_symbols()
+    assert declared == set(lib.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(l, name) is not None
+
+
+def test_select_and_advantage_argument_checks():
+    l = lib.load()
+    one = ctypes.c_void_p(256)   # never dereferenced: every case below fails validation first
+    assert l.pods_select(None, 1, 4, 2, one, None, None) == 1
+    assert "null" in lib.pods_last_error()
+    assert l.pods_select(one, 1, 4, 5, one, None, None) == 1          # m > n
+    assert l.pods_select(one, 0, 4, 2, one, None, None) == 1
+    assert l.pods_select(one, 1, 4, 0, one, None, None) == 1
+    assert l.pods_select(one, 1, 5000, 2, one, None, None) == 2       # n beyond the kernels' limit
+    assert l.pods_advantage(one, None, 1, 4, 2, 0.0, one, None) == 1
+    assert l.pods_advantage(one, one, 1, 4, 5, 0.0, one, None) == 1
+    assert l.pods_advantage(one, one, 1, 4, 2, -1.0, one, None) == 1
+
+
+def test_loss_argument_checks_and_workspace_query():
+    l = lib.load()
+    one = ctypes.c_void_p(256)
+    args = lambda **kw: [kw.get("hidden", one), one, one, one, one, None, kw.get("R", 2), 8, kw.get("d", 64), 100,
+                         kw.get("dt", 1), kw.get("eps", 0.2), 1.0, one, None, one, one, kw.get("ws", one),
+                         kw.get("wsb", 1 << 40), None]
+    assert l.grpo_token_loss_fwd_bwd(*args(hidden=None)) == 1
+    assert l.grpo_token_loss_fwd_bwd(*args(R=0)) == 1
+    assert l.grpo_token_loss_fwd_bwd(*args(eps=-0.1)) == 1
+    assert l.grpo_token_loss_fwd_bwd(*args(dt=7)) == 1
+    assert l.grpo_token_loss_fwd_bwd(*args(d=20000)) == 2
+    assert l.grpo_token_loss_fwd_bwd(*args(ws=None)) == 3
+    assert l.grpo_token_loss_fwd_bwd(*args(ws=ctypes.c_void_p(264))) == 3      # misaligned
+    assert l.grpo_token_loss_fwd_bwd(*args(wsb=16)) == 3
+    assert "workspace" in lib.pods_last_error()
+    need = lib.grpo_token_loss_workspace_bytes(512, 1024, 2048, 151936, lib.PODS_BF16)
+    least = lib.grpo_token_loss_workspace_min_bytes(512, 1024, 2048, 151936, lib.PODS_BF16)
+    assert 0 < least <= need < 64 << 30
+    assert lib.grpo_token_loss_workspace_bytes(0, 1, 1, 1, 0) == 0
+    assert lib.grpo_token_loss_workspace_bytes(16, 64, 256, 1024, lib.PODS_F32) > 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2504_13818_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libpods_hip.so")
+    with pytest.raises(FileNotFoundError):
+        binding.load()

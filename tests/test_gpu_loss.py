@@ -1,0 +1,68 @@
+"""GPU parity: grpo_token_loss_fwd_bwd through the C ABI against the CPU oracle
+(loss, log-probs, d_hidden, d_w_lm within 2e-3 relative / 1e-4 absolute, plus norm-wise checks)."""
+import numpy as np
+import pytest
+
+from paper_2504_13818_amd import inputs
+from tests import helpers as H
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def test_config0_fp32_full(pods):
+    """B=4, m=4 -> R=16 rollouts, T=64, d=256, V=1024, fp32; oracle in fp64."""
+    case = H.loss_case(0, 16, 64, 256, 1024, sigma=0.05, gemm_dtype=np.float64)
+    H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case, gemm_dtype=np.float64))
+
+
+def test_config0_fp32_clipping_active_and_unit_scale(pods):
+    case = H.loss_case(0, 16, 64, 256, 1024, sigma=0.3, gemm_dtype=np.float64)
+    scale = 16 * 64.0
+    got = H.gpu_loss(pods, torch, case, grad_scale=scale)
+    ref = H.oracle_loss(case, grad_scale=scale, gemm_dtype=np.float64)
+    H.check_loss(got, ref)
+    assert (np.abs(ref["d_hidden"]).sum(axis=-1) == 0).any()      # some tokens really were clipped
+    zero_rows = np.abs(ref["d_hidden"]).sum(axis=-1) == 0
+    assert np.all(got["d_hidden"][zero_rows] == 0)
+
+
+def test_fp32_ragged_odd_shapes(pods):
+    case = H.loss_case(0, 5, 37, 100, 333, sigma=0.3, gemm_dtype=np.float64)
+    case["lengths"][2] = 0                                        # an empty rollout still counts in R
+    H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case, gemm_dtype=np.float64))
+
+
+@pytest.mark.parametrize("R,T,d,V", [(6, 96, 256, 1000), (3, 300, 512, 2500), (9, 64, 192, 777)])
+def test_bf16_small_shapes(pods, R, T, d, V):
+    """bf16 matrix-core path at sizes spanning several tiles with ragged tails in every dimension."""
+    case = H.loss_case(1, R, T, d, V, sigma=0.2)
+    H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case))
+    scale = float(R * case["lengths"].mean())
+    H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale))
+
+
+def test_bf16_small_workspace_many_chunks(pods):
+    case = H.loss_case(4, 4, 128, 256, 3000, sigma=0.2)
+    ws = torch.empty((pods.grpo_token_loss_workspace_min_bytes(4, 128, 256, 3000, pods.PODS_BF16),),
+                     dtype=torch.uint8, device="cuda")
+    H.check_loss(H.gpu_loss(pods, torch, case, workspace=ws), H.oracle_loss(case))
+
+
+def test_bf16_no_lengths_and_determinism(pods):
+    case = H.loss_case(1, 4, 128, 256, 1500, sigma=0.2, ragged=False)
+    a = H.gpu_loss(pods, torch, case, use_lengths=False)
+    b = H.gpu_loss(pods, torch, case, use_lengths=True)
+    H.check_loss(a, H.oracle_loss(case))
+    for key in ("logp", "d_hidden", "d_w"):
+        assert np.array_equal(a[key], b[key])
+    assert a["loss"] == b["loss"]
+
+
+@pytest.mark.parametrize("cfg,R,T", [(1, 4, 320), (2, 2, 400), (4, 6, 160)])
+def test_bf16_full_head_reduced_tokens(pods, cfg, R, T):
+    """Full d and V of the config (lm_head shape), a few hundred valid tokens."""
+    c = inputs.CONFIGS[cfg]
+    case = H.loss_case(cfg, R, T, c["d"], c["V"], sigma=0.05)
+    scale = float(R * case["lengths"].mean())
+    H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale))
