@@ -1,0 +1,220 @@
+"""Benchmark of the PODS hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: pods_select -> pods_advantage ->
+grpo_token_loss_fwd_bwd, with every input already resident in HBM.  The default workload is the
+Qwen2.5-3B-shaped head (B=32 prompt groups, n=64 -> m=16, T=1024 ragged, d=2048, V=151936, bf16).
+Prints ONE JSON line: whole-step valid-token throughput, the roofline of the dominant kernel
+(timed live with HIP events around each launch), the selector's bandwidth figures on the
+selector-stress workload, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 / fp16 MFMA peak
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
+
+
+def current_logp_torch(torch, hidden, w, tokens, chunk=4096):
+    """log-softmax(hidden . w^T)[token] with plain torch ops, in token chunks (input synthesis only:
+    old_logp is an input of the path, defined as the current log-prob plus noise)."""
+    R, T, d = hidden.shape
+    h2 = hidden.reshape(R * T, d)
+    tok = tokens.reshape(R * T).long()
+    out = torch.empty(R * T, dtype=torch.float32, device=hidden.device)
+    for s in range(0, R * T, chunk):
+        z = (h2[s:s + chunk] @ w.T).float()
+        out[s:s + chunk] = z.gather(1, tok[s:s + chunk, None])[:, 0] - torch.logsumexp(z, dim=1)
+    return out.reshape(R, T)
+
+
+def time_selector(lib, torch, inputs, steps):
+    """pods_select on the selector-stress workload (B=65536, n=256, m=64), rotating over enough
+    buffer sets that no input or output is served from the 256 MiB Infinity Cache."""
+    import numpy as np
+    c = inputs.CONFIGS[3]
+    B, n, m = c["B"], c["n"], c["m"]
+    r = torch.from_numpy(inputs.rewards(3)).cuda()
+    sets = 6                                    # 6 x (64 + 16) MiB
+    rs = [r.clone() for _ in range(sets)]
+    idx = [torch.empty((B, m), dtype=torch.int32, device="cuda") for _ in range(sets)]
+    ks = [torch.empty((B,), dtype=torch.int32, device="cuda") for _ in range(sets)]
+    for i in range(sets):
+        lib.pods_select(rs[i], m, idx[i], ks[i])
+    torch.cuda.synchronize()
+    lib.pods_profile_enable(True)
+    reps = max(steps, 3) * sets
+    for i in range(reps):
+        lib.pods_select(rs[i % sets], m, idx[i % sets], ks[i % sets])
+    prof = lib.pods_profile_read()
+    lib.pods_profile_enable(False)
+    ms = float(np.mean([t for _, t in prof]))
+    bytes_per_group = 4 * n + 4 * m + 4
+    gbs = bytes_per_group * B / (ms * 1e-3) / 1e9
+    return dict(workload="selector-stress B=65536 n=256 m=64 fp32", ms_per_launch=ms,
+                groups_per_s=B / (ms * 1e-3), launches=len(prof),
+                roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
+                              frac=gbs / PEAK_HBM_GBS, traffic=None,
+                              bytes_per_group=bytes_per_group))
+
+
+def cpu_selector(inputs):
+    from oracle import fast
+    r = inputs.rewards(3)
+    fast.select(r[:1024], 64)
+    t = time.perf_counter()
+    _, _, used = fast.select(r, 64)
+    dt = time.perf_counter() - t
+    return dict(value=r.shape[0] / dt, unit="groups/s", cores=int(used), kind="oracle",
+                sample="all 65536 groups of the selector-stress workload, C oracle, OpenMP")
+
+
+def cpu_loss(inputs, cfg, tokens_sample=1024):
+    """The numpy oracle (fp32 GEMM, fp64 reductions) forward + backward on a bounded sample."""
+    import numpy as np
+    from oracle import pods_oracle as po
+    c = inputs.CONFIGS[cfg]
+    R, T = 2, tokens_sample // 2
+    h, w = inputs.dense(cfg, R, T, c["d"], c["V"])
+    tok = inputs.tokens(cfg, R, T, c["V"])
+    adv = np.array([1.0, -1.0], np.float32)
+    old = np.full((R, T), -12.0, np.float32)
+    t = time.perf_counter()
+    po.grpo_token_loss(h, w, tok, old, adv, None, c["clip_eps"], gemm_dtype=np.float32)
+    dt = time.perf_counter() - t
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return dict(value=R * T / dt, unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=f"{R * T} valid tokens ({R} rollouts x {T}) at full d={c['d']}, V={c['V']}; "
+                       f"fp32 GEMM, fp64 reductions; forward + backward, {dt:.1f} s; cost is linear in tokens")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=1, choices=[1, 2, 4])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
+              "(groups and rollouts shard across GPUs without exchange; see DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2504_13818_amd as lib
+    from paper_2504_13818_amd import inputs
+
+    lib.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = args.config
+    c = inputs.CONFIGS[cfg]
+    B, n, m, T, d, V = c["B"], c["n"], c["m"], c["T"], c["d"], c["V"]
+    R = B * m
+
+    rewards = torch.from_numpy(inputs.rewards(cfg)).to(dev)
+    lens_np = inputs.lengths(cfg)
+    n_valid = int(lens_np.sum())
+    lengths = torch.from_numpy(lens_np).to(dev)
+    tokens = torch.from_numpy(inputs.tokens(cfg, R, T, V)).to(dev)
+    hidden, w = inputs.dense_torch(cfg, dev)
+    cur = current_logp_torch(torch, hidden, w, tokens)
+    g = torch.Generator(device=dev)
+    g.manual_seed(inputs.seed_for(cfg, 5))
+    old_logp = (cur + 0.05 * torch.randn(cur.shape, generator=g, device=dev)).contiguous()
+    del cur
+
+    dt = lib.PODS_BF16 if c["dtype"] == "bf16" else lib.PODS_F32
+    ws = torch.empty((lib.grpo_token_loss_workspace_bytes(R, T, d, V, dt),), dtype=torch.uint8, device=dev)
+    out = dict(loss=torch.empty(1, dtype=torch.float32, device=dev),
+               logp=torch.empty((R, T), dtype=torch.float32, device=dev),
+               d_hidden=torch.empty((R, T, d), dtype=torch.float32, device=dev),
+               d_w_lm=torch.empty((V, d), dtype=torch.float32, device=dev))
+    sel_idx = torch.empty((B, m), dtype=torch.int32, device=dev)
+    sel_k = torch.empty((B,), dtype=torch.int32, device=dev)
+    adv = torch.empty((B, m), dtype=torch.float32, device=dev)
+
+    def step():
+        lib.pods_select(rewards, m, sel_idx, sel_k)
+        lib.pods_advantage(rewards, sel_idx, 0.0, adv)
+        lib.grpo_token_loss_fwd_bwd(hidden, w, tokens, old_logp, adv.view(-1), lengths, c["clip_eps"],
+                                    1.0, workspace=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    lib.pods_profile_enable(True)               # HIP events around every launch, on the launch stream
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = lib.pods_profile_read()
+    lib.pods_profile_enable(False)
+    ms_per_step = wall * 1e3 / args.steps
+    loss_val = float(out["loss"].cpu()[0])
+    assert np.isfinite(loss_val)
+
+    per = {}
+    for name, ms in prof:
+        e = per.setdefault(name, [0, 0.0])
+        e[0] += 1
+        e[1] += ms
+    kernels = {k: dict(launches_per_step=v[0] / args.steps, ms_per_step=v[1] / args.steps,
+                       avg_ms=v[1] / v[0]) for k, v in per.items()}
+    gemm_names = ["token loss forward", "token loss recompute", "token loss d_hidden", "token loss d_w_lm"]
+    flops_family = 2.0 * n_valid * d * V        # each of the four contractions, per step
+    for k in gemm_names:
+        if k in kernels:
+            kernels[k]["tflops"] = flops_family / (kernels[k]["ms_per_step"] * 1e-3) / 1e12
+    dominant = max((k for k in gemm_names if k in kernels), key=lambda k: kernels[k]["ms_per_step"])
+    dk = kernels[dominant]
+    flops_per_launch = flops_family / dk["launches_per_step"]
+    achieved = flops_per_launch / (dk["avg_ms"] * 1e-3) / 1e12
+    gpu_ms = sum(v["ms_per_step"] for v in kernels.values())
+    roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                    flops_per_launch=flops_per_launch, avg_launch_ms=dk["avg_ms"],
+                    path_executed_tflops=4 * flops_family / (gpu_ms * 1e-3) / 1e12,
+                    path_executed_frac=4 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                    path_model_frac=3 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
+
+    selector = time_selector(lib, torch, inputs, args.steps)
+    result = {
+        "metric": "GRPO token-loss fwd+bwd tokens/s (% MFMA peak); pods_select groups/s (% HBM)",
+        "value": n_valid / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": c["dtype"], "data": "synthetic",
+        "config": {"workload": f"configs[{cfg}] {c['name']}: B={B} n={n} m={m} R={R} T={T} "
+                               f"valid_tokens={n_valid} d={d} V={V} {c['dtype']} eps={c['clip_eps']}",
+                   "step": "pods_select + pods_advantage + grpo_token_loss_fwd_bwd"},
+        "roofline": roofline,
+        "kernels": kernels,
+        "selector": selector,
+        "loss": loss_val,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_loss(inputs, cfg)
+        result["selector"]["cpu_baseline"] = cpu_selector(inputs)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

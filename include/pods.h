@@ -109,8 +109,10 @@ size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int3
  *   workspace 256-byte aligned device buffer of workspace_bytes; contents undefined after the call
  *
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; softmax statistics are
- * fp32; the per-logit gradient is rounded to bf16 before the two gradient contractions.
- * fp32 inputs use fp32 arithmetic throughout.  d <= 16384.
+ * fp32.  For the two gradient contractions the softmax part of the per-logit gradient is rounded
+ * to fp16 (scaled so that it cannot overflow) and the generated token's own logit is applied in
+ * fp32; results are deterministic (no floating-point atomics).  A bf16 call with d not a multiple
+ * of 64, and every fp32 call, uses plain fp32 vector arithmetic throughout.  d <= 16384.
  */
 pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const int32_t* tokens,
                                     const float* old_logp, const float* adv, const int32_t* lengths,
@@ -118,6 +120,16 @@ pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const 
                                     float clip_eps, float grad_scale, float* loss, float* logp_out,
                                     float* d_hidden, float* d_w_lm, void* workspace,
                                     size_t workspace_bytes, void* stream);
+
+/* Per-launch timing for benchmarks (not part of the method).  pods_profile_enable(1) makes every
+ * later library call on this thread bracket each of its kernel launches with a pair of HIP events
+ * on the call's stream, and discards earlier records; pods_profile_enable(0) stops recording.
+ * pods_profile_count() is the number of launches recorded so far; pods_profile_get(i, ...) waits for
+ * launch i to finish (the only call here that synchronises with the device) and returns the
+ * kernel's name (a static host string) and its duration in milliseconds. */
+pods_status pods_profile_enable(int32_t enable);
+int32_t pods_profile_count(void);
+pods_status pods_profile_get(int32_t i, const char** name, float* ms);
 
 /* Host string for the last error on the calling thread; valid until the next failing call. */
 const char* pods_last_error(void);

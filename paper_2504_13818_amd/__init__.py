@@ -7,10 +7,11 @@ fails, an exception is raised.
 """
 from .binding import (PodsError, load, library_path, pods_select, pods_advantage,
                       grpo_token_loss_fwd_bwd, grpo_token_loss_workspace_bytes,
-                      grpo_token_loss_workspace_min_bytes, pods_last_error, PODS_F32, PODS_BF16,
-                      EXPORTED_SYMBOLS)
+                      grpo_token_loss_workspace_min_bytes, pods_last_error, pods_profile_enable,
+                      pods_profile_read, PODS_F32, PODS_BF16, EXPORTED_SYMBOLS)
 
 __all__ = ["PodsError", "load", "library_path", "pods_select", "pods_advantage",
            "grpo_token_loss_fwd_bwd", "grpo_token_loss_workspace_bytes",
-           "grpo_token_loss_workspace_min_bytes", "pods_last_error", "PODS_F32", "PODS_BF16",
+           "grpo_token_loss_workspace_min_bytes", "pods_last_error", "pods_profile_enable",
+           "pods_profile_read", "PODS_F32", "PODS_BF16",
            "EXPORTED_SYMBOLS"]

@@ -11,7 +11,7 @@ _lib = None
 PODS_F32, PODS_BF16 = 0, 1
 EXPORTED_SYMBOLS = ("pods_select", "pods_advantage", "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
-                    "pods_last_error")
+                    "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
 
 _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
 
@@ -48,8 +48,31 @@ def load():
     lib.grpo_token_loss_fwd_bwd.restype = ctypes.c_int
     lib.grpo_token_loss_fwd_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                             ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.pods_profile_enable.restype = ctypes.c_int
+    lib.pods_profile_enable.argtypes = [_i32]
+    lib.pods_profile_count.restype = _i32
+    lib.pods_profile_count.argtypes = []
+    lib.pods_profile_get.restype = ctypes.c_int
+    lib.pods_profile_get.argtypes = [_i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_f32)]
     _lib = lib
     return lib
+
+
+def pods_profile_enable(enable: bool = True):
+    """Bracket every later kernel launch of this thread's library calls with HIP events."""
+    _check(load().pods_profile_enable(1 if enable else 0))
+
+
+def pods_profile_read():
+    """[(kernel name, milliseconds)] for every launch recorded since pods_profile_enable(True).
+    Waits for the recorded launches to finish."""
+    lib = load()
+    out = []
+    name, ms = ctypes.c_char_p(), _f32()
+    for i in range(lib.pods_profile_count()):
+        _check(lib.pods_profile_get(i, ctypes.byref(name), ctypes.byref(ms)))
+        out.append((name.value.decode(), float(ms.value)))
+    return out
 
 
 def pods_last_error() -> str:

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void advantage_kernel(
 pods_status launch_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
                              int32_t m, float std_eps, float* adv, hipStream_t stream) {
     const unsigned grid = (unsigned)ceil_div(B, kWavesPerBlock);
-    hipLaunchKernelGGL(advantage_kernel, dim3(grid), dim3(kWavesPerBlock * kWave), 0, stream,
+    PODS_LAUNCH("pods_advantage", stream, advantage_kernel, dim3(grid), dim3(kWavesPerBlock * kWave), 0, stream,
                        rewards, sel_idx, B, n, m, std_eps, adv);
     return check_launch("pods_advantage");
 }

@@ -30,6 +30,22 @@ inline pods_status check_launch(const char* what) {
     return PODS_OK;
 }
 
+// Optional per-launch timing (pods_profile_*): when enabled on the calling thread, every kernel
+// launch made through a StageTimer scope is bracketed by a pair of HIP events on its stream.
+void profile_stage_begin(const char* name, hipStream_t stream);
+void profile_stage_end(hipStream_t stream);
+struct StageTimer {
+    hipStream_t stream;
+    StageTimer(const char* name, hipStream_t s) : stream(s) { profile_stage_begin(name, s); }
+    ~StageTimer() { profile_stage_end(stream); }
+};
+
+#define PODS_LAUNCH(name, strm, ...)                        \
+    do {                                                    \
+        ::pods::StageTimer pods_stage_timer_(name, strm);   \
+        hipLaunchKernelGGL(__VA_ARGS__);                    \
+    } while (0)
+
 constexpr int kWave = 64;  // CDNA wavefront width
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

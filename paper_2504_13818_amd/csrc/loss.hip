@@ -235,14 +235,14 @@ pods_status run_loss(const LossArgs& a) {
     auto* loss_part = reinterpret_cast<double*>(ws + p.off_losspart);
     pods_status st;
 
-    hipLaunchKernelGGL(scan_lengths_kernel, dim3(1), dim3(1024), 0, a.stream, a.lengths, a.R, a.T,
+    PODS_LAUNCH("scan_lengths", a.stream, scan_lengths_kernel, dim3(1), dim3(1024), 0, a.stream, a.lengths, a.R, a.T,
                        offsets, hdr);
     if ((st = check_launch("scan_lengths")) != PODS_OK) return st;
-    hipLaunchKernelGGL(fill_rows_kernel, dim3((unsigned)ceil_div(a.T, 256), (unsigned)a.R), dim3(256),
+    PODS_LAUNCH("fill_rows", a.stream, fill_rows_kernel, dim3((unsigned)ceil_div(a.T, 256), (unsigned)a.R), dim3(256),
                        0, a.stream, a.lengths, a.tokens, offsets, a.T, row_map, tok, a.logp_out);
     if ((st = check_launch("fill_rows")) != PODS_OK) return st;
     if (a.lengths != nullptr) {
-        hipLaunchKernelGGL(zero_pad_rows_kernel, dim3((unsigned)p.ncap), dim3(256), 0, a.stream,
+        PODS_LAUNCH("zero_pad_rows", a.stream, zero_pad_rows_kernel, dim3((unsigned)p.ncap), dim3(256), 0, a.stream,
                            a.lengths, a.T, a.d, a.d_hidden);
         if ((st = check_launch("zero_pad_rows")) != PODS_OK) return st;
     }
@@ -250,11 +250,11 @@ pods_status run_loss(const LossArgs& a) {
     st = p.mfma ? mfma_forward(a, p) : simple_forward(a, p);
     if (st != PODS_OK) return st;
 
-    hipLaunchKernelGGL(surrogate_kernel, dim3((unsigned)p.loss_blocks), dim3(256), 0, a.stream, hdr,
+    PODS_LAUNCH("surrogate", a.stream, surrogate_kernel, dim3((unsigned)p.loss_blocks), dim3(256), 0, a.stream, hdr,
                        row_map, pmax, psum, p.slots, p.ncap_ld, zy, a.old_logp, a.adv, a.lengths, a.R,
                        a.T, a.clip_eps, a.grad_scale, lse, g, coef, a.logp_out, loss_part);
     if ((st = check_launch("surrogate")) != PODS_OK) return st;
-    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(1024), 0, a.stream, loss_part,
+    PODS_LAUNCH("finalize_loss", a.stream, finalize_loss_kernel, dim3(1), dim3(1024), 0, a.stream, loss_part,
                        p.loss_blocks, a.loss);
     if ((st = check_launch("finalize_loss")) != PODS_OK) return st;
 

@@ -25,11 +25,10 @@
 // almost entirely inside a lane, and the gradient tiles store four consecutive k per lane.
 //
 // Workgroup: 256 threads = 4 waves as 2x2, each wave a 128x128 sub-tile (4x4 MFMA blocks, 256
-// accumulator registers).  K is walked in tiles of 64 through a double-buffered LDS stage of
-// 2 x (256 + 256) rows x 128 B; 16-byte granules within a row are XOR-swizzled by (row & 7) so
-// that the ds_read_b128 fragment loads are conflict-free.  Workgroup ids are mapped to tiles so
-// that the 32 workgroups resident on one XCD (one L2) form a 4 x 8 block of tiles and share
-// operand rows.
+// accumulator registers).  K is walked in tiles of 32 through a ring of four LDS stages of
+// (256 + 256) rows x 64 B, filled by direct-to-LDS global loads three tiles ahead (see k_loop).
+// Workgroup ids are mapped to tiles so that the 32 workgroups resident on one XCD (one L2) form a
+// 4 x 8 block of tiles and share operand rows.
 #include "loss.h"
 
 namespace pods {
@@ -42,69 +41,72 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBK = 64;                            // k per LDS stage
-constexpr int kOperandBytes = kTile * kBK * 2;     // 32 KiB: 256 rows x 128 B
+constexpr int kBK = 32;                            // k per LDS stage
+constexpr int kOperandBytes = kTile * kBK * 2;     // 16 KiB: 256 rows x 64 B
 constexpr int kStageBytes = 2 * kOperandBytes;     // A then B
-constexpr int kLdsBytes = 2 * kStageBytes;         // double buffer: 128 KiB
+constexpr int kStages = 4;                         // ring of LDS stages
+constexpr int kDist = kStages - 1;                 // k-tiles in flight ahead of the one being multiplied
+constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kXcds = 8;
 constexpr int kSuper0 = 4, kSuper1 = 8;            // tiles per XCD block along the two tile axes
 
-struct Operand {  // this thread's 8 row pointers (bytes) into one 256-row operand tile
-    const unsigned char* ptr[8];
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// s_waitcnt vmcnt(N), leaving expcnt and lgkmcnt alone (gfx9 encoding).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// Global -> LDS without passing through registers (global_load_lds_dwordx4): one wave instruction
+// deposits 64 lanes x 16 B at consecutive LDS addresses, i.e. 16 rows of a 64-byte-row tile.  Lane l
+// of wave w, instruction i fills row 64 i + 16 w + l/4, slot l%4, and therefore fetches the granule
+// (l%4) ^ ((row >> 2) & 3) of that row: the XOR swizzle that makes the later ds_read_b128 fragment
+// loads (16 consecutive rows, one granule column per pass) hit 16 distinct bank groups.
+struct Operand {  // this thread's 4 row pointers (bytes) into one 256-row operand tile
+    const unsigned char* ptr[4];
 };
 
-// Rows row0 + tid/8 + 32 i, granule tid%8; rows at or beyond `rows` are clamped to the last row
-// (their products are masked or multiplied by zeros by the caller).
+// Rows at or beyond `rows` are clamped to the last row (their products are masked or multiplied
+// by zeros by the caller).
 __device__ __forceinline__ void operand_rows(Operand& op, const uint16_t* base, int64_t ld,
                                              int64_t row0, int64_t rows, int64_t col0,
                                              const int32_t* __restrict__ gather) {
-    const int r = threadIdx.x >> 3, gc = threadIdx.x & 7;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int gc = (l & 3) ^ ((l >> 4) & 3);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int64_t row = row0 + r + 32 * i;
+    for (int i = 0; i < 4; ++i) {
+        int64_t row = row0 + 64 * i + 16 * w + (l >> 2);
         if (row >= rows) row = rows - 1;
         if (gather != nullptr) row = gather[row];
         op.ptr[i] = reinterpret_cast<const unsigned char*>(base + row * ld + col0 + gc * 8);
     }
 }
-
-__device__ __forceinline__ void load_operand(const Operand& op, u32x4 (&stg)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) stg[i] = *reinterpret_cast<const u32x4*>(op.ptr[i]);
-}
 __device__ __forceinline__ void advance(Operand& op, int64_t bytes) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) op.ptr[i] += bytes;
-}
-__device__ __forceinline__ void store_operand(unsigned char* lds_operand, int wr_off,
-                                              const u32x4 (&stg)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<u32x4*>(lds_operand + wr_off + i * 4096) = stg[i];
+    for (int i = 0; i < 4; ++i) op.ptr[i] += bytes;
 }
 
 struct LaneGeom {
-    int wr_off;   // LDS byte offset of this thread's granule in row tid/8 (+ i*4096 per row group)
     int a_rd;     // LDS byte offset of this lane's A-role fragment row (wave's first block)
-    int b_rd;     // same for the B role
+    int b_rd;     // same for the B role (includes the operand offset within a stage)
     int cx16;     // swizzle term of the fragment granule
     int wm, wn;   // wave position in the 2x2 wave grid
-    int lane;
+    int lane, wave;
 };
 
 __device__ __forceinline__ LaneGeom lane_geom() {
     LaneGeom g;
     const int tid = threadIdx.x;
     g.lane = tid & 63;
-    const int wave = tid >> 6;
-    g.wm = wave >> 1;
-    g.wn = wave & 1;
-    const int r = tid >> 3, gc = tid & 7;
-    g.wr_off = r * 128 + ((gc ^ (r & 7)) << 4);
-    g.a_rd = (g.wm * 128 + (g.lane & 31)) * 128;
-    g.b_rd = (g.wn * 128 + (g.lane & 31)) * 128;
-    g.cx16 = ((g.lane >> 5) ^ (g.lane & 7)) << 4;
+    g.wave = tid >> 6;
+    g.wm = g.wave >> 1;
+    g.wn = g.wave & 1;
+    g.a_rd = (g.wm * 128 + (g.lane & 31)) * 64;
+    g.b_rd = kOperandBytes + (g.wn * 128 + (g.lane & 31)) * 64;
+    g.cx16 = ((g.lane >> 5) ^ ((g.lane >> 2) & 3)) << 4;
     return g;
 }
 
@@ -115,58 +117,94 @@ __device__ __forceinline__ f32x16 mfma(f16x8 a, f16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-// One LDS stage (k = 64): four k-steps of 4 + 4 fragment loads and 16 MFMAs.  E is the operand
-// element vector type (bf16x8 for the logits, f16x8 for the gradient contractions).
-template <typename E>
-__device__ __forceinline__ void mma_stage(const unsigned char* stage, const LaneGeom& g,
-                                          f32x16 (&acc)[4][4]) {
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        const int ko = (ks * 32) ^ g.cx16;
-        E af[4], bfr[4];
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-            af[mi] = *reinterpret_cast<const E*>(stage + g.a_rd + mi * 4096 + ko);
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-            bfr[ni] = *reinterpret_cast<const E*>(stage + kOperandBytes + g.b_rd + ni * 4096 + ko);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma(af[mi], bfr[ni], acc[mi][ni]);
-    }
-}
-
-// acc += A[256 x (64 KT)] . B[256 x (64 KT)]^T.  On return both operands have advanced 128 KT bytes
-// and every wave has left the LDS stage.
+// acc += A[256 x (32 KT)] . B[256 x (32 KT)]^T.  E is the operand element vector (bf16x8 for the
+// logits, f16x8 for the gradient contractions).
+//
+// Each k-tile (32 deep = two MFMA k-steps) lives in one stage of a ring of kStages LDS stages;
+// kDist tiles are always in flight.  One iteration multiplies tile kt in two phases of 16 MFMAs:
+//   phase 0: MFMAs on fragment set F0 (k-step 0, read during the previous iteration), interleaved
+//            one-for-one with the 8 direct-to-LDS loads of tile kt+kDist (into the stage consumed
+//            in the previous iteration) and the 8 fragment reads of F1 (k-step 1);
+//   then     wait until this wave's share of tile kt+1 has landed, workgroup barrier;
+//   phase 1: MFMAs on F1, interleaved with the 8 fragment reads of tile kt+1's F0.
+// The interleaving is pinned with scheduling barriers: left alone, the compiler issues the loads
+// back to back, and the matrix pipe idles while the vector-memory queue drains.  Past the last
+// tile the loads repeat the last tile into stages nobody reads again, so the loop body stays
+// branch-free.  On return each operand pointer rests on its last tile, nothing is in flight, and
+// the LDS ring may be reused after a barrier.
 template <typename E>
 __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned char* lds,
                                        const LaneGeom& g, f32x16 (&acc)[4][4]) {
-    u32x4 sa[8], sb[8];
-    load_operand(A, sa);
-    load_operand(B, sb);
-    advance(A, 128);
-    advance(B, 128);
-    store_operand(lds, g.wr_off, sa);
-    store_operand(lds + kOperandBytes, g.wr_off, sb);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        unsigned char* cur = lds + (kt & 1) * kStageBytes;
-        unsigned char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            load_operand(A, sa);
-            load_operand(B, sb);
-            advance(A, 128);
-            advance(B, 128);
+    unsigned char* wave_base = lds + g.wave * 1024;
+    const int ko0 = g.cx16, ko1 = 32 ^ g.cx16;
+    int issued = 0;
+    E fa[2][4], fb[2][4];
+    __builtin_amdgcn_s_barrier();   // every wave has left the ring (previous use)
+#pragma unroll
+    for (int t = 0; t < kDist; ++t) {
+        const int adv = (issued + 1 < KT) ? 64 : 0;
+        unsigned char* dst = wave_base + t * kStageBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_global_load_lds(A.ptr[i], (lds_ptr_t)(dst + i * 4096), 16, 0, 0);
+            A.ptr[i] += adv;
         }
-        mma_stage<E>(cur, g, acc);
-        if (more) {
-            store_operand(nxt, g.wr_off, sa);
-            store_operand(nxt + kOperandBytes, g.wr_off, sb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_global_load_lds(B.ptr[i], (lds_ptr_t)(dst + kOperandBytes + i * 4096), 16, 0, 0);
+            B.ptr[i] += adv;
         }
-        __syncthreads();
+        ++issued;
     }
+    wait_vmcnt<8 * (kDist - 1)>();
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        fa[0][i] = *reinterpret_cast<const E*>(lds + g.a_rd + i * 2048 + ko0);
+        fb[0][i] = *reinterpret_cast<const E*>(lds + g.b_rd + i * 2048 + ko0);
+    }
+    int st = 0, fill = kDist;
+    for (int kt = 0; kt < KT; ++kt) {
+        const unsigned char* cur = lds + st * kStageBytes;
+        const int stn = (st + 1 == kStages) ? 0 : st + 1;
+        const unsigned char* nxt = lds + stn * kStageBytes;
+        unsigned char* dst = wave_base + fill * kStageBytes;
+        const int adv = (issued + 1 < KT) ? 64 : 0;
+        ++issued;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
+            if (i < 4) {
+                __builtin_amdgcn_global_load_lds(A.ptr[i], (lds_ptr_t)(dst + i * 4096), 16, 0, 0);
+                A.ptr[i] += adv;
+            } else {
+                __builtin_amdgcn_global_load_lds(B.ptr[i - 4], (lds_ptr_t)(dst + kOperandBytes + (i - 4) * 4096), 16, 0, 0);
+                B.ptr[i - 4] += adv;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
+            if (i < 4) fa[1][i] = *reinterpret_cast<const E*>(cur + g.a_rd + i * 2048 + ko1);
+            else fb[1][i - 4] = *reinterpret_cast<const E*>(cur + g.b_rd + (i - 4) * 2048 + ko1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_vmcnt<8 * (kDist - 1)>();   // loads return in order: everything but the newest kDist-1 tiles is in LDS
+        wait_lgkmcnt0();                 // this wave's reads of `cur` are done before others may refill it
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
+            { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
+            if (i < 4) fa[0][i] = *reinterpret_cast<const E*>(nxt + g.a_rd + i * 2048 + ko0);
+            else fb[0][i - 4] = *reinterpret_cast<const E*>(nxt + g.b_rd + (i - 4) * 2048 + ko0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        st = stn;
+        fill = (fill + 1 == kStages) ? 0 : fill + 1;
+    }
+    wait_vmcnt<0>();
+    wait_lgkmcnt0();
 }
 
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
@@ -242,7 +280,7 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
         zero_acc(acc);
         operand_rows(A, w, d, (int64_t)vt * kTile, V, 0, nullptr);
         k_loop<bf16x8>(A, B, KT, lds, g, acc);
-        advance(B, -(int64_t)KT * 128);
+        advance(B, -(int64_t)(KT - 1) * 64);   // back to the first k-tile
 
         const int vbase = vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // row of (mi=0, r=0)
         if (vt * kTile + kTile > V) {  // last, partial vocabulary tile: rows >= V do not exist
@@ -601,7 +639,7 @@ pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
     const int64_t ntt = p.ncap_ld / kTile;
     const int64_t groups = (ntt + 3) / 4;                                // 4 token tiles each
     const int64_t grid = (groups + kXcds - 1) / kXcds * kXcds * 32;
-    hipLaunchKernelGGL(fwd_kernel, dim3((unsigned)grid), dim3(256), kLdsBytes, a.stream,
+    PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)grid), dim3(256), kLdsBytes, a.stream,
                        reinterpret_cast<const LossHeader*>(ws + p.off_hdr),
                        reinterpret_cast<const int32_t*>(ws + p.off_rowmap),
                        reinterpret_cast<const int32_t*>(ws + p.off_tok),
@@ -632,14 +670,14 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
     if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
 
     const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
-    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)(p.vld / 64), dtiles64), dim3(256), 0, a.stream,
+    PODS_LAUNCH("transpose W", a.stream, transpose_kernel, dim3((unsigned)(p.vld / 64), dtiles64), dim3(256), 0, a.stream,
                        hdr, nullptr, nullptr, w, (int64_t)a.V, a.d, p.vld, 0, wt);
     if ((st = check_launch("transpose W")) != PODS_OK) return st;
-    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
+    PODS_LAUNCH("transpose H", a.stream, transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
                        a.stream, hdr, row_map, g, hidden, (int64_t)0, a.d, p.ncap_ld, 1, ht);
     if ((st = check_launch("transpose H")) != PODS_OK) return st;
 
-    hipLaunchKernelGGL(dh_onehot_kernel, dim3((unsigned)ceil_div(p.ncap, 4)), dim3(256), 0, a.stream, hdr,
+    PODS_LAUNCH("token loss d_hidden (y logit)", a.stream, dh_onehot_kernel, dim3((unsigned)ceil_div(p.ncap, 4)), dim3(256), 0, a.stream, hdr,
                        row_map, tok, coef, w, a.d, a.d_hidden);
     if ((st = check_launch("token loss d_hidden (y logit)")) != PODS_OK) return st;
 
@@ -649,20 +687,20 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
     for (int c = 0; c < p.nchunks; ++c) {
         const int v0 = c * p.vc;
         if (v0 >= a.V) break;
-        hipLaunchKernelGGL(recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
+        PODS_LAUNCH("token loss recompute", a.stream, recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
                            kLdsBytes, a.stream, hdr, row_map, tok, lse, hidden, w, a.d, a.V, v0, p.vc,
                            p.ncap_ld, dz, dzt);
         if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
-        hipLaunchKernelGGL(dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
+        PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
                            a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(wt), p.vld,
                            reinterpret_cast<const uint16_t*>(dz), a.d, v0, p.vc, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
-        hipLaunchKernelGGL(dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
+        PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
                            kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(ht),
                            reinterpret_cast<const uint16_t*>(dzt), p.ncap_ld, a.d, a.V, v0, p.vc, a.d_w_lm);
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
     }
-    hipLaunchKernelGGL(dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,
+    PODS_LAUNCH("token loss d_w_lm (y logit)", a.stream, dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,
                        a.stream, hdr, row_map, tok, coef, hidden, a.d, a.V, a.d_w_lm);
     return check_launch("token loss d_w_lm (y logit)");
 }

@@ -177,7 +177,7 @@ pods_status forward_t(const LossArgs& a, const LossPlan& p) {
     auto kernel = simple_fwd_kernel<E>;
     pods_status st = reserve_lds(kernel, lds, "token loss forward (plain)");
     if (st != PODS_OK) return st;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)p.ncap), dim3(256), lds, a.stream,
+    PODS_LAUNCH("token loss forward (plain)", a.stream, kernel, dim3((unsigned)p.ncap), dim3(256), lds, a.stream,
                        reinterpret_cast<const LossHeader*>(ws + p.off_hdr),
                        reinterpret_cast<const int32_t*>(ws + p.off_rowmap),
                        reinterpret_cast<const int32_t*>(ws + p.off_tok),
@@ -203,11 +203,11 @@ pods_status backward_t(const LossArgs& a, const LossPlan& p) {
     if (st != PODS_OK) return st;
     st = reserve_lds(kdw, lds, "token loss d_w_lm (plain)");
     if (st != PODS_OK) return st;
-    hipLaunchKernelGGL(kdh, dim3((unsigned)p.ncap), dim3(256), lds, a.stream, hdr, row_map, tok, lse,
+    PODS_LAUNCH("token loss d_hidden (plain)", a.stream, kdh, dim3((unsigned)p.ncap), dim3(256), lds, a.stream, hdr, row_map, tok, lse,
                        g, static_cast<const E*>(a.hidden), static_cast<const E*>(a.w_lm), a.d, a.V,
                        a.d_hidden);
     if ((st = check_launch("token loss d_hidden (plain)")) != PODS_OK) return st;
-    hipLaunchKernelGGL(kdw, dim3((unsigned)a.V), dim3(256), lds, a.stream, hdr, row_map, tok, lse, g,
+    PODS_LAUNCH("token loss d_w_lm (plain)", a.stream, kdw, dim3((unsigned)a.V), dim3(256), lds, a.stream, hdr, row_map, tok, lse, g,
                        static_cast<const E*>(a.hidden), static_cast<const E*>(a.w_lm), a.d, a.V,
                        a.d_w_lm);
     return check_launch("token loss d_w_lm (plain)");

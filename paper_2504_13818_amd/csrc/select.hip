@@ -225,7 +225,7 @@ pods_status launch_variant(const float* rewards, int32_t B, int32_t n, int32_t m
                         hipGetErrorString(e));
     }
     const unsigned grid = (unsigned)ceil_div(B, WAVES);
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(WAVES * kWave), lds, stream, rewards, B, n, m,
+    PODS_LAUNCH("pods_select", stream, kernel, dim3(grid), dim3(WAVES * kWave), lds, stream, rewards, B, n, m,
                        sel_idx, sel_k);
     return check_launch("pods_select");
 }
