@@ -56,15 +56,15 @@ constexpr int kDefaultVocabChunk = 8192;
 
 struct LossPlan {
     int64_t ncap;     // R*T
-    int64_t ncap_ld;  // ncap rounded up to kTile: leading dimension of token-contiguous arrays
+    int64_t ncap_ld;  // ncap rounded up to kTile: rows of the per-token arrays
     bool mfma;        // bf16 inputs with d % 64 == 0 take the matrix-core path
     int slots;        // forward partial slots per token
     int vc;           // vocabulary chunk of the backward pass (multiple of kTile); 0 on the plain path
     int nchunks;
-    int64_t vld;      // leading dimension of the transposed weight = nchunks * vc
+    int64_t vld;      // rows of the fp16 weight copy = nchunks * vc (zero past V)
     int loss_blocks;
     size_t off_hdr, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_pmax, off_psum,
-        off_losspart, off_wt, off_ht, off_dz, off_dzt, total;
+        off_losspart, off_wt, off_ht, off_dz, total;
 };
 
 // mode 0: recommended size; mode 1: minimum size; otherwise `mode` is the number of bytes

@@ -31,12 +31,12 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     p.off_losspart = take(sizeof(double) * (size_t)p.loss_blocks);
     if (!p.mfma) {
         p.vc = 0; p.nchunks = 0; p.vld = 0;
-        p.off_wt = p.off_ht = p.off_dz = p.off_dzt = off;
+        p.off_wt = p.off_ht = p.off_dz = off;
         p.total = off;
         return p;
     }
     const int64_t vround = ((int64_t)V + kTile - 1) / kTile * kTile;
-    // Fixed part: transposed weight (needs vld, at most vround + vc) and transposed packed hidden.
+    // Fixed part: fp16 weight copy (vld rows, at most vround + vc) and fp16 packed, g-scaled hidden.
     auto total_for = [&](int vc, LossPlan& q) {
         size_t o = off;
         auto tk = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
@@ -46,7 +46,6 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
         q.off_wt = tk(2 * (size_t)d * (size_t)q.vld);
         q.off_ht = tk(2 * (size_t)d * (size_t)p.ncap_ld);
         q.off_dz = tk(2 * (size_t)p.ncap_ld * (size_t)vc);
-        q.off_dzt = tk(2 * (size_t)vc * (size_t)p.ncap_ld);
         q.total = o;
     };
     int vc;

@@ -4,22 +4,24 @@
 // operands contiguous along k, computed by one workgroup per 256x256 output tile with
 // v_mfma_f32_32x32x16_bf16 and fp32 accumulators:
 //
-//   forward    z[v][t]  = sum_k W[v][k]  H[t][k]        -> running (max, sum exp) per token, z_y
-//   recompute  z[v][t]  (same)                          -> q = -2^14 exp(z - lse) as fp16 (0 at v = y),
-//                                                          stored token-major and vocab-major
-//   d_hidden   dH[k][t] = sum_v Wt[k][v] q[t][v]        -> times g_t, accumulated over vocab chunks
-//   d_w_lm     dW[k][v] = sum_t Ht[k][t] qT[v][t]       -> complete per vocabulary chunk
+//   forward    z[v][t]  = sum_k W[v][k]   H[t][k]       -> running (max, sum exp) per token, z_y
+//   recompute  z[v][t]  (same)                          -> q = -2^14 exp(z - lse) as fp16 (0 at v = y)
+//   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times g_t, accumulated over vocab chunks
+//   d_w_lm     dW[k][v] = sum_t H16[t][k] q[t][v]       -> complete per vocabulary chunk
+//
+// An operand whose contraction index is its row index in memory (W16 in d_hidden, both operands
+// in d_w_lm) is staged in LDS as it lies in memory and read with the transposing LDS load, so q is
+// stored once (token-major) and no transposed copy of any matrix exists.
 //
 // The per-logit gradient is dz = g_t q / 2^14 for v != y.  q is kept in fp16 (11-bit significand)
 // rather than bf16 (8-bit) so that a logit with a large probability does not carry a 2^-8 error
 // into its token's gradient.  The token weight g_t, which spans many binades, never enters q:
-// d_hidden applies it per output row, and d_w_lm folds it into Ht = fp16(g_t h_t 2^-e) with one
-// global power-of-two range scale.  Wt = fp16(256 W) is an exact copy of the bf16 weight.
+// d_hidden applies it per output row, and d_w_lm folds it into H16 = fp16(g_t h_t 2^-e) with one
+// global power-of-two range scale.  W16 = fp16(256 W) is an exact copy of the bf16 weight.
 // The generated token's own logit, dz_y = g (1 - softmax_y), dominates each token's gradient and
 // is kept out of the rounded operands altogether: its two rank-one terms, dz_y W_y into d_hidden
 // and dz_y h_t into row y of d_w_lm, are added in fp32 by two small kernels (exact bf16 products,
-// fixed summation order, no atomics).
-// (Wt, Ht are transposes made once per call so that every product is NT.)  The first
+// fixed summation order, no atomics).  The first
 // operand ("A role") indexes accumulator rows: a lane of the 32x32 MFMA result holds one column j
 // and rows 8b + 4(lane/32) + c, so the reduction over the vocabulary in the forward pass is
 // almost entirely inside a lane, and the gradient tiles store four consecutive k per lane.
@@ -53,6 +55,25 @@ constexpr int kSuper0 = 4, kSuper1 = 8;            // tiles per XCD block along 
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
+// global_load_lds_dwordx4: each lane fetches 16 B from its own global address; the wave's 64 x 16 B
+// land at consecutive LDS addresses starting at `lds_dst` (wave-uniform, carried in M0).  Issued as
+// inline assembly so that the compiler does not pair it with the LDS reads it schedules (it would
+// drain the whole vector-memory queue before each of them); completion is tracked by hand with
+// s_waitcnt vmcnt.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_to_lds_16_asm(const unsigned char* gptr, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+// kernels whose LDS reads are all plain ds_read_b128 may use the builtin (no spurious waits there)
+template <bool ASM>
+__device__ __forceinline__ void load_to_lds_16(const unsigned char* gptr, unsigned char* lds_generic,
+                                               unsigned lds_addr) {
+    if constexpr (ASM) load_to_lds_16_asm(gptr, lds_addr);
+    else __builtin_amdgcn_global_load_lds(gptr, (lds_ptr_t)lds_generic, 16, 0, 0);
+}
+
 // s_waitcnt vmcnt(N), leaving expcnt and lgkmcnt alone (gfx9 encoding).
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -65,12 +86,14 @@ __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC
 // of wave w, instruction i fills row 64 i + 16 w + l/4, slot l%4, and therefore fetches the granule
 // (l%4) ^ ((row >> 2) & 3) of that row: the XOR swizzle that makes the later ds_read_b128 fragment
 // loads (16 consecutive rows, one granule column per pass) hit 16 distinct bank groups.
-struct Operand {  // this thread's 4 row pointers (bytes) into one 256-row operand tile
+struct Operand {  // this thread's 4 source pointers (bytes) into one operand k-tile, and the k-tile stride
     const unsigned char* ptr[4];
+    int64_t step;
 };
 
-// Rows at or beyond `rows` are clamped to the last row (their products are masked or multiplied
-// by zeros by the caller).
+// Operand stored with the contraction index contiguous ("row-major rows x k"): tile = 256 rows x
+// 64 B.  Rows at or beyond `rows` are clamped to the last row (their products are masked or
+// multiplied by zeros by the caller).
 __device__ __forceinline__ void operand_rows(Operand& op, const uint16_t* base, int64_t ld,
                                              int64_t row0, int64_t rows, int64_t col0,
                                              const int32_t* __restrict__ gather) {
@@ -83,17 +106,41 @@ __device__ __forceinline__ void operand_rows(Operand& op, const uint16_t* base, 
         if (gather != nullptr) row = gather[row];
         op.ptr[i] = reinterpret_cast<const unsigned char*>(base + row * ld + col0 + gc * 8);
     }
+    op.step = 64;
 }
+
+// Operand stored with the contraction index as the ROW index ("k x columns", columns contiguous):
+// tile = 32 k-rows x 256 columns (512 B per row); it is read back through the transposing LDS load
+// (ds_read_b64_tr_b16), so no transposed copy of the matrix is ever made.  One wave instruction
+// deposits two rows; lane l of wave w, instruction i fills row 8i + 2w + l/32, slot l%32, and
+// fetches the granule (l%32) ^ ((row & 3) << 2): four consecutive k-rows then sit in four different
+// 64-byte bank quarters, which is what the transposing read touches at once.
+// Columns at or beyond `cols` (a multiple of 8) are clamped to the last granule (masked by the caller).
+__device__ __forceinline__ void operand_kmajor(Operand& op, const uint16_t* base, int64_t ld,
+                                               int64_t k0, int64_t col0, int64_t cols) {
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 8 * i + 2 * w + (l >> 5);
+        const int gc = (l & 31) ^ ((row & 3) << 2);
+        int64_t col = col0 + gc * 8;
+        if (col > cols - 8) col = cols - 8;
+        op.ptr[i] = reinterpret_cast<const unsigned char*>(base + (k0 + row) * ld + col);
+    }
+    op.step = 32 * ld * 2;
+}
+
 __device__ __forceinline__ void advance(Operand& op, int64_t bytes) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) op.ptr[i] += bytes;
 }
 
 struct LaneGeom {
-    int a_rd;     // LDS byte offset of this lane's A-role fragment row (wave's first block)
-    int b_rd;     // same for the B role (includes the operand offset within a stage)
-    int cx16;     // swizzle term of the fragment granule
-    int wm, wn;   // wave position in the 2x2 wave grid
+    int a_rd, b_rd;   // row-major operands: LDS byte offset of this lane's fragment row (first block)
+    int cx16;         // ... and the swizzle term of its fragment granule
+    int a_km, b_km;   // k-major operands: LDS byte offset of this lane's transposing-read source
+    int e6;           // ... and its swizzle term ((k row & 3) << 6)
+    int wm, wn;       // wave position in the 2x2 wave grid
     int lane, wave;
 };
 
@@ -107,6 +154,13 @@ __device__ __forceinline__ LaneGeom lane_geom() {
     g.a_rd = (g.wm * 128 + (g.lane & 31)) * 64;
     g.b_rd = kOperandBytes + (g.wn * 128 + (g.lane & 31)) * 64;
     g.cx16 = ((g.lane >> 5) ^ ((g.lane >> 2) & 3)) << 4;
+    // transposing read: within a block of 16 lanes, source lane j = 4e + q supplies 4 consecutive
+    // columns of k-row e; result lane i receives column i of rows e = 0..3
+    const int blk = g.lane >> 4, kg = blk >> 1, e = (g.lane >> 2) & 3, q = g.lane & 3;
+    const int km = (kg * 8 + e) * 512 + (q & 1) * 8 + ((blk & 1) * 2 + (q >> 1)) * 16;
+    g.a_km = km + g.wm * 256;
+    g.b_km = kOperandBytes + km + g.wn * 256;
+    g.e6 = e << 6;
     return g;
 }
 
@@ -117,42 +171,65 @@ __device__ __forceinline__ f32x16 mfma(f16x8 a, f16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-// acc += A[256 x (32 KT)] . B[256 x (32 KT)]^T.  E is the operand element vector (bf16x8 for the
-// logits, f16x8 for the gradient contractions).
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
+
+// Fragment (32 rows x 16 k, 8 elements per lane) of MFMA block `blk`, k-step `ks`, from a stage.
+template <typename E, bool KM>
+__device__ __forceinline__ E read_frag(const unsigned char* stage, int rd, int km, int e6, int cx16,
+                                       int blk, int ks) {
+    if constexpr (!KM) {
+        return *reinterpret_cast<const E*>(stage + rd + blk * 2048 + ((ks * 32) ^ cx16));
+    } else {
+        const unsigned char* p = stage + km + (e6 ^ (blk << 6)) + ks * 8192;
+        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p));
+        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p + 2048));
+        const i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(E, both);
+    }
+}
+
+// acc += A . B^T over KT k-tiles of 32.  E is the operand element vector (bf16x8 for the logits,
+// f16x8 for the gradient contractions); AKM / BKM say which operands are k-major (see Operand).
 //
-// Each k-tile (32 deep = two MFMA k-steps) lives in one stage of a ring of kStages LDS stages;
-// kDist tiles are always in flight.  One iteration multiplies tile kt in two phases of 16 MFMAs:
+// Each k-tile (two MFMA k-steps) lives in one stage of a ring of kStages LDS stages; kDist tiles
+// are always in flight.  One iteration multiplies tile kt in two phases of 16 MFMAs:
 //   phase 0: MFMAs on fragment set F0 (k-step 0, read during the previous iteration), interleaved
-//            one-for-one with the 8 direct-to-LDS loads of tile kt+kDist (into the stage consumed
-//            in the previous iteration) and the 8 fragment reads of F1 (k-step 1);
+//            with the 8 direct-to-LDS loads of tile kt+kDist (into the stage consumed in the
+//            previous iteration) and the fragment reads of F1 (k-step 1);
 //   then     wait until this wave's share of tile kt+1 has landed, workgroup barrier;
-//   phase 1: MFMAs on F1, interleaved with the 8 fragment reads of tile kt+1's F0.
+//   phase 1: MFMAs on F1, interleaved with the fragment reads of tile kt+1's F0.
 // The interleaving is pinned with scheduling barriers: left alone, the compiler issues the loads
 // back to back, and the matrix pipe idles while the vector-memory queue drains.  Past the last
 // tile the loads repeat the last tile into stages nobody reads again, so the loop body stays
 // branch-free.  On return each operand pointer rests on its last tile, nothing is in flight, and
 // the LDS ring may be reused after a barrier.
-template <typename E>
+template <typename E, bool AKM = false, bool BKM = false>
 __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned char* lds,
                                        const LaneGeom& g, f32x16 (&acc)[4][4]) {
+    constexpr bool kAsm = AKM || BKM;
     unsigned char* wave_base = lds + g.wave * 1024;
-    const int ko0 = g.cx16, ko1 = 32 ^ g.cx16;
+    const unsigned wave_lds = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)wave_base);
     int issued = 0;
     E fa[2][4], fb[2][4];
     __builtin_amdgcn_s_barrier();   // every wave has left the ring (previous use)
 #pragma unroll
     for (int t = 0; t < kDist; ++t) {
-        const int adv = (issued + 1 < KT) ? 64 : 0;
+        const bool more = issued + 1 < KT;
+        const int64_t adva = more ? A.step : 0, advb = more ? B.step : 0;
         unsigned char* dst = wave_base + t * kStageBytes;
+        const unsigned dsta = wave_lds + t * kStageBytes;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_global_load_lds(A.ptr[i], (lds_ptr_t)(dst + i * 4096), 16, 0, 0);
-            A.ptr[i] += adv;
+            load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
+            A.ptr[i] += adva;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_global_load_lds(B.ptr[i], (lds_ptr_t)(dst + kOperandBytes + i * 4096), 16, 0, 0);
-            B.ptr[i] += adv;
+            load_to_lds_16<kAsm>(B.ptr[i], dst + kOperandBytes + i * 4096, dsta + kOperandBytes + i * 4096);
+            B.ptr[i] += advb;
         }
         ++issued;
     }
@@ -160,8 +237,8 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        fa[0][i] = *reinterpret_cast<const E*>(lds + g.a_rd + i * 2048 + ko0);
-        fb[0][i] = *reinterpret_cast<const E*>(lds + g.b_rd + i * 2048 + ko0);
+        fa[0][i] = read_frag<E, AKM>(lds, g.a_rd, g.a_km, g.e6, g.cx16, i, 0);
+        fb[0][i] = read_frag<E, BKM>(lds, g.b_rd, g.b_km, g.e6, g.cx16, i, 0);
     }
     int st = 0, fill = kDist;
     for (int kt = 0; kt < KT; ++kt) {
@@ -169,23 +246,26 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
         const int stn = (st + 1 == kStages) ? 0 : st + 1;
         const unsigned char* nxt = lds + stn * kStageBytes;
         unsigned char* dst = wave_base + fill * kStageBytes;
-        const int adv = (issued + 1 < KT) ? 64 : 0;
+        const unsigned dsta = wave_lds + fill * kStageBytes;
+        const bool more = issued + 1 < KT;
+        const int64_t adva = more ? A.step : 0, advb = more ? B.step : 0;
         ++issued;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
             if (i < 4) {
-                __builtin_amdgcn_global_load_lds(A.ptr[i], (lds_ptr_t)(dst + i * 4096), 16, 0, 0);
-                A.ptr[i] += adv;
+                load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
+                A.ptr[i] += adva;
             } else {
-                __builtin_amdgcn_global_load_lds(B.ptr[i - 4], (lds_ptr_t)(dst + kOperandBytes + (i - 4) * 4096), 16, 0, 0);
-                B.ptr[i - 4] += adv;
+                load_to_lds_16<kAsm>(B.ptr[i - 4], dst + kOperandBytes + (i - 4) * 4096,
+                                     dsta + kOperandBytes + (i - 4) * 4096);
+                B.ptr[i - 4] += advb;
             }
             __builtin_amdgcn_sched_barrier(0);
             { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
-            if (i < 4) fa[1][i] = *reinterpret_cast<const E*>(cur + g.a_rd + i * 2048 + ko1);
-            else fb[1][i - 4] = *reinterpret_cast<const E*>(cur + g.b_rd + (i - 4) * 2048 + ko1);
+            if (i < 4) fa[1][i] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, i, 1);
+            else fb[1][i - 4] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, i - 4, 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         wait_vmcnt<8 * (kDist - 1)>();   // loads return in order: everything but the newest kDist-1 tiles is in LDS
@@ -196,8 +276,8 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
         for (int i = 0; i < 8; ++i) {
             { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
             { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
-            if (i < 4) fa[0][i] = *reinterpret_cast<const E*>(nxt + g.a_rd + i * 2048 + ko0);
-            else fb[0][i - 4] = *reinterpret_cast<const E*>(nxt + g.b_rd + (i - 4) * 2048 + ko0);
+            if (i < 4) fa[0][i] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, i, 0);
+            else fb[0][i - 4] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, i - 4, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         st = stn;
@@ -349,13 +429,13 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 
 // ------------------------------------------------------------------------------------------
 // Backward step 1 (per vocabulary chunk): recompute the logits tile and form
-// q = -kQScale exp(z - lse), rounded to fp16, 0 at v = y, in both layouts (dz = g q / kQScale).
+// q = -kQScale exp(z - lse), rounded to fp16, 0 at v = y, token-major (dz = g q / kQScale).
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void recompute_kernel(
     const LossHeader* __restrict__ hdr, const int32_t* __restrict__ row_map,
     const int32_t* __restrict__ tok, const float* __restrict__ lse,
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int d, int V, int v0,
-    int vc, int64_t ncap_ld, _Float16* __restrict__ q, _Float16* __restrict__ qt) {
+    int vc, _Float16* __restrict__ q) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
@@ -413,20 +493,18 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
                 for (int c = 0; c < 4; ++c) pk[c] = (_Float16)val[mi][b * 4 + c];
                 const int vl = vloc + mi * 32 + 8 * b;
                 *reinterpret_cast<f16x4*>(q + p * vc + vl) = pk;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) qt[(int64_t)(vl + c) * ncap_ld + p] = pk[c];
             }
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward step 2: d_hidden[t][k] += (g_t / (kQScale kWScale)) sum_{v in chunk} q[t][v] Wt[k][v]
+// Backward step 2: d_hidden[t][k] += (g_t / (kQScale kWScale)) sum_{v in chunk} q[t][v] W16[v][k]
 // (the rows were initialised with the y-logit term)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict__ hdr,
                                                     const int32_t* __restrict__ row_map,
                                                     const float* __restrict__ gvec,
-                                                    const uint16_t* __restrict__ wt, int64_t vld,
+                                                    const uint16_t* __restrict__ w16,
                                                     const uint16_t* __restrict__ q, int d, int v0,
                                                     int vc, float* __restrict__ d_hidden) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -437,12 +515,12 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     const LaneGeom g = lane_geom();
 
     Operand A, B;
-    operand_rows(A, wt, vld, kt0 * kTile, d, v0, nullptr);
+    operand_kmajor(A, w16, d, v0, kt0 * kTile, d);   // rows v >= V of W16 are zero
     // every row of the last token tile was written by the recompute step (zeros past N)
     operand_rows(B, q, vc, tt * kTile, ntt * kTile, 0, nullptr);
     f32x16 acc[4][4];
     zero_acc(acc);
-    k_loop<f16x8>(A, B, vc / kBK, lds, g, acc);
+    k_loop<f16x8, true, false>(A, B, vc / kBK, lds, g, acc);
 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
@@ -466,13 +544,13 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward step 3: d_w_lm[v][k] = (1 / (kQScale s)) sum_t qT[v][t] Ht[k][t], Ht = g_t h_t s
+// Backward step 3: d_w_lm[v][k] = (1 / (kQScale s)) sum_t q[t][v] H16[t][k], H16 = g_t h_t s
 // (all tokens: complete per chunk)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict__ hdr,
-                                                    const uint16_t* __restrict__ ht,
-                                                    const uint16_t* __restrict__ qt,
-                                                    int64_t ncap_ld, int d, int V, int v0, int vc,
+                                                    const uint16_t* __restrict__ h16,
+                                                    const uint16_t* __restrict__ q,
+                                                    int d, int V, int v0, int vc,
                                                     float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
@@ -482,12 +560,13 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
     const LaneGeom g = lane_geom();
 
     Operand A, B;
-    operand_rows(A, ht, ncap_ld, kt0 * kTile, d, 0, nullptr);
-    operand_rows(B, qt, ncap_ld, vt * kTile, vc, 0, nullptr);
+    // token rows past N (up to the end of the last token tile) are zero in both operands
+    operand_kmajor(A, h16, d, 0, kt0 * kTile, d);
+    operand_kmajor(B, q, vc, 0, vt * kTile, vc);
     f32x16 acc[4][4];
     zero_acc(acc);
     const int KT = (n_valid + kBK - 1) / kBK;
-    if (KT > 0) k_loop<f16x8>(A, B, KT, lds, g, acc);
+    if (KT > 0) k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
     const float scale = 1.0f / (kQScale * g_range_scale(hdr));
 
 #pragma unroll
@@ -584,44 +663,44 @@ __global__ __launch_bounds__(256) void dw_onehot_kernel(const LossHeader* __rest
 }
 
 // ------------------------------------------------------------------------------------------
-// fp16 transposed copies (once per call):
-//   Wt[k][v] = kWScale W[v][k]            (zero for v >= V; exact: bf16 has fewer significand bits)
-//   Ht[k][p] = s g_p H[row_map[p]][k]     (zero for p >= N up to the end of the last token tile;
+// fp16 operand copies (once per call):
+//   W16[v][k] = kWScale W[v][k]           (zero rows for v >= V; exact: bf16 has fewer significand bits)
+//   H16[p][k] = s g_p H[row_map[p]][k]    (zero rows for p >= N up to the end of the last token tile;
 //                                          s = the global range scale of g)
+// One thread per 8 elements.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void transpose_kernel(const LossHeader* __restrict__ hdr,
-                                                        const int32_t* __restrict__ gather,
-                                                        const float* __restrict__ gvec,
-                                                        const uint16_t* __restrict__ src, int64_t rows,
-                                                        int d, int64_t ld_out, int token_rows,
-                                                        _Float16* __restrict__ dst) {
-    __shared__ _Float16 tile[64][66];
-    int64_t nrows = rows;
-    int64_t fill_to = ld_out;
+__global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restrict__ hdr,
+                                                      const int32_t* __restrict__ gather,
+                                                      const float* __restrict__ gvec,
+                                                      const uint16_t* __restrict__ src, int64_t rows,
+                                                      int64_t rows_out, int d, int token_rows,
+                                                      _Float16* __restrict__ dst) {
+    int64_t nrows = rows, fill_to = rows_out;
     float common = kWScale;
     if (token_rows) {
         nrows = hdr->n_valid;
         fill_to = (nrows + kTile - 1) / kTile * kTile;
         common = g_range_scale(hdr);
     }
-    const int64_t r0 = (int64_t)blockIdx.x * 64;
-    const int k0 = blockIdx.y * 64;
-    if (r0 >= fill_to) return;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rr = ty; rr < 64; rr += 4) {
-        const int64_t r = r0 + rr;
-        float x = 0.0f;
-        if (r < nrows && k0 + tx < d) {
-            const int64_t srow = gather ? (int64_t)gather[r] : r;
-            x = __uint_as_float((uint32_t)src[srow * d + k0 + tx] << 16) * common;
-            if (token_rows) x *= gvec[r];
+    const int per_row = d / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t r = idx / per_row;
+    const int k = (int)(idx % per_row) * 8;
+    if (r >= fill_to) return;
+    f16x8 out;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) out[j] = (_Float16)0.0f;
+    if (r < nrows) {
+        const int64_t srow = gather ? (int64_t)gather[r] : r;
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(src + srow * d + k);
+        const float sc = token_rows ? common * gvec[r] : common;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            out[2 * j] = (_Float16)(__uint_as_float(raw[j] << 16) * sc);
+            out[2 * j + 1] = (_Float16)(__uint_as_float(raw[j] & 0xFFFF0000u) * sc);
         }
-        tile[rr][tx] = (_Float16)x;
     }
-    __syncthreads();
-    for (int kk = ty; kk < 64; kk += 4) {
-        if (k0 + kk < d && r0 + tx < ld_out) dst[(int64_t)(k0 + kk) * ld_out + r0 + tx] = tile[tx][kk];
-    }
+    *reinterpret_cast<f16x8*>(dst + r * d + k) = out;
 }
 
 pods_status reserve(const void* kernel, const char* what) {
@@ -658,10 +737,9 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
     auto* lse = reinterpret_cast<const float*>(ws + p.off_lse);
     auto* g = reinterpret_cast<const float*>(ws + p.off_g);
     auto* coef = reinterpret_cast<const float*>(ws + p.off_coef);
-    auto* wt = reinterpret_cast<_Float16*>(ws + p.off_wt);
-    auto* ht = reinterpret_cast<_Float16*>(ws + p.off_ht);
+    auto* w16 = reinterpret_cast<_Float16*>(ws + p.off_wt);
+    auto* h16 = reinterpret_cast<_Float16*>(ws + p.off_ht);
     auto* dz = reinterpret_cast<_Float16*>(ws + p.off_dz);
-    auto* dzt = reinterpret_cast<_Float16*>(ws + p.off_dzt);
     const auto* hidden = static_cast<const uint16_t*>(a.hidden);
     const auto* w = static_cast<const uint16_t*>(a.w_lm);
     pods_status st;
@@ -669,13 +747,13 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
     if ((st = reserve(reinterpret_cast<const void*>(dh_kernel), "token loss d_hidden")) != PODS_OK) return st;
     if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
 
-    const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
-    PODS_LAUNCH("transpose W", a.stream, transpose_kernel, dim3((unsigned)(p.vld / 64), dtiles64), dim3(256), 0, a.stream,
-                       hdr, nullptr, nullptr, w, (int64_t)a.V, a.d, p.vld, 0, wt);
-    if ((st = check_launch("transpose W")) != PODS_OK) return st;
-    PODS_LAUNCH("transpose H", a.stream, transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
-                       a.stream, hdr, row_map, g, hidden, (int64_t)0, a.d, p.ncap_ld, 1, ht);
-    if ((st = check_launch("transpose H")) != PODS_OK) return st;
+    const int64_t per_row = a.d / 8;
+    PODS_LAUNCH("convert W", a.stream, convert_kernel, dim3((unsigned)ceil_div(p.vld * per_row, 256)), dim3(256), 0,
+                a.stream, hdr, nullptr, nullptr, w, (int64_t)a.V, p.vld, a.d, 0, w16);
+    if ((st = check_launch("convert W")) != PODS_OK) return st;
+    PODS_LAUNCH("convert H", a.stream, convert_kernel, dim3((unsigned)ceil_div(p.ncap_ld * per_row, 256)), dim3(256), 0,
+                a.stream, hdr, row_map, g, hidden, (int64_t)0, p.ncap_ld, a.d, 1, h16);
+    if ((st = check_launch("convert H")) != PODS_OK) return st;
 
     PODS_LAUNCH("token loss d_hidden (y logit)", a.stream, dh_onehot_kernel, dim3((unsigned)ceil_div(p.ncap, 4)), dim3(256), 0, a.stream, hdr,
                        row_map, tok, coef, w, a.d, a.d_hidden);
@@ -688,16 +766,15 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
         const int v0 = c * p.vc;
         if (v0 >= a.V) break;
         PODS_LAUNCH("token loss recompute", a.stream, recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
-                           kLdsBytes, a.stream, hdr, row_map, tok, lse, hidden, w, a.d, a.V, v0, p.vc,
-                           p.ncap_ld, dz, dzt);
+                           kLdsBytes, a.stream, hdr, row_map, tok, lse, hidden, w, a.d, a.V, v0, p.vc, dz);
         if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
-                           a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(wt), p.vld,
+                           a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
                            reinterpret_cast<const uint16_t*>(dz), a.d, v0, p.vc, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
-                           kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(ht),
-                           reinterpret_cast<const uint16_t*>(dzt), p.ncap_ld, a.d, a.V, v0, p.vc, a.d_w_lm);
+                           kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(h16),
+                           reinterpret_cast<const uint16_t*>(dz), a.d, a.V, v0, p.vc, a.d_w_lm);
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
     }
     PODS_LAUNCH("token loss d_w_lm (y logit)", a.stream, dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,
