@@ -47,7 +47,8 @@ __device__ __forceinline__ float g_range_scale(const LossHeader* hdr) {
 
 // Fixed power-of-two scales of the fp16 operands of the two gradient contractions.
 constexpr float kQScale = 16384.0f;  // q = kQScale (1[v=y] - softmax): |q| <= 2^14
-constexpr float kWScale = 256.0f;    // transposed weight copy holds kWScale * W
+constexpr float kWScale = 256.0f;    // fp16 weight copies hold kWScale * W
+constexpr float kHScale = 0.0625f;   // fp16 transposed hidden copy holds kHScale * h
 
 constexpr int kTile = 256;          // token / vocab / hidden tile edge of the matrix-core kernels
 constexpr int kFwdVocabSplits = 8;  // vocabulary splits of the forward pass (one per XCD slot)
@@ -62,9 +63,10 @@ struct LossPlan {
     int vc;           // vocabulary chunk of the backward pass (multiple of kTile); 0 on the plain path
     int nchunks;
     int64_t vld;      // rows of the fp16 weight copy = nchunks * vc (zero past V)
+    int64_t vld_t;    // columns of the transposed fp16 weight copy = V rounded up to kTile
     int loss_blocks;
     size_t off_hdr, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_pmax, off_psum,
-        off_losspart, off_wt, off_ht, off_dz, total;
+        off_losspart, off_wtt, off_htt, off_wt, off_ht, off_dz, total;
 };
 
 // mode 0: recommended size; mode 1: minimum size; otherwise `mode` is the number of bytes

@@ -30,12 +30,15 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     p.off_psum = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
     p.off_losspart = take(sizeof(double) * (size_t)p.loss_blocks);
     if (!p.mfma) {
-        p.vc = 0; p.nchunks = 0; p.vld = 0;
-        p.off_wt = p.off_ht = p.off_dz = off;
+        p.vc = 0; p.nchunks = 0; p.vld = 0; p.vld_t = 0;
+        p.off_wtt = p.off_htt = p.off_wt = p.off_ht = p.off_dz = off;
         p.total = off;
         return p;
     }
     const int64_t vround = ((int64_t)V + kTile - 1) / kTile * kTile;
+    p.vld_t = vround;
+    p.off_wtt = take(2 * (size_t)d * (size_t)vround);        // transposed fp16 weight, [vround/256][d][256]
+    p.off_htt = take(2 * (size_t)d * (size_t)p.ncap_ld);     // transposed fp16 hidden, [ncap_ld/256][d][256]
     // Fixed part: fp16 weight copy (vld rows, at most vround + vc) and fp16 packed, g-scaled hidden.
     auto total_for = [&](int vc, LossPlan& q) {
         size_t o = off;

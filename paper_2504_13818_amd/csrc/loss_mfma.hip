@@ -50,6 +50,7 @@ constexpr int kStages = 4;                         // ring of LDS stages
 constexpr int kDist = kStages - 1;                 // k-tiles in flight ahead of the one being multiplied
 constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kInvLogitScale = 1.0f / (kWScale * kHScale);   // logits are accumulated as kWScale kHScale z
 constexpr int kXcds = 8;
 constexpr int kSuper0 = 4, kSuper1 = 8;            // tiles per XCD block along the two tile axes
 
@@ -324,12 +325,12 @@ __device__ __forceinline__ int acc_slot_of(int rel) {
 // Forward: per token, (max, sum exp) over this workgroup's share of the vocabulary, and z_y.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restrict__ hdr,
-                                                     const int32_t* __restrict__ row_map,
                                                      const int32_t* __restrict__ tok,
-                                                     const uint16_t* __restrict__ hidden,
-                                                     const uint16_t* __restrict__ w, int d, int V,
-                                                     int64_t slot_stride, float* __restrict__ pmax,
-                                                     float* __restrict__ psum, float* __restrict__ zy) {
+                                                     const uint16_t* __restrict__ ht,
+                                                     const uint16_t* __restrict__ wt,
+                                                     int d, int V, int64_t slot_stride,
+                                                     float* __restrict__ pmax, float* __restrict__ psum,
+                                                     float* __restrict__ zy) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     // ids congruent mod 8 (one XCD): 4 token tiles x 8 vocabulary splits
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
     const int KT = d / kBK;
 
     Operand A, B;
-    operand_rows(B, hidden, d, tt * kTile, n_valid, 0, row_map);
+    operand_kmajor(B, ht + tt * d * kTile, kTile, 0, 0, kTile);
 
     int y[4];
     float M[4], L[4];
@@ -358,9 +359,9 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
     f32x16 acc[4][4];
     for (int vt = vs; vt < nvt; vt += kFwdVocabSplits) {
         zero_acc(acc);
-        operand_rows(A, w, d, (int64_t)vt * kTile, V, 0, nullptr);
-        k_loop<bf16x8>(A, B, KT, lds, g, acc);
-        advance(B, -(int64_t)(KT - 1) * 64);   // back to the first k-tile
+        operand_kmajor(A, wt + (int64_t)vt * d * kTile, kTile, 0, 0, kTile);
+        k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
+        advance(B, -(int64_t)(KT - 1) * B.step);   // back to the first k-tile
 
         const int vbase = vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // row of (mi=0, r=0)
         if (vt * kTile + kTile > V) {  // last, partial vocabulary tile: rows >= V do not exist
@@ -386,14 +387,14 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
                         if (slot == mi * 16 + r) val = acc[mi][ni][r];
-                if (slot >= 0) zy[tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31)] = val;
+                if (slot >= 0) zy[tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31)] = val * kInvLogitScale;
             }
             float m = acc[0][ni][0];
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[mi][ni][r]);
-            const float Mn = fmaxf(M[ni], m);
+            const float Mn = fmaxf(M[ni], m * kInvLogitScale);   // accumulators hold kLogitScale * z
             const float Ms = (Mn == -__builtin_huge_valf()) ? 0.0f : Mn;
             const float off = -Ms * kLog2e;
             float s = 0.0f;
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    s += __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e, off));
+                    s += __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e * kInvLogitScale, off));
             L[ni] = L[ni] * __builtin_amdgcn_exp2f(fmaf(M[ni], kLog2e, off)) + s;
             M[ni] = Mn;
         }
@@ -432,10 +433,10 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 // q = -kQScale exp(z - lse), rounded to fp16, 0 at v = y, token-major (dz = g q / kQScale).
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void recompute_kernel(
-    const LossHeader* __restrict__ hdr, const int32_t* __restrict__ row_map,
-    const int32_t* __restrict__ tok, const float* __restrict__ lse,
-    const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ w, int d, int V, int v0,
-    int vc, _Float16* __restrict__ q) {
+    const LossHeader* __restrict__ hdr, const int32_t* __restrict__ tok,
+    const float* __restrict__ lse, const uint16_t* __restrict__ ht,
+    const uint16_t* __restrict__ wt, int d, int V, int v0, int vc,
+    _Float16* __restrict__ q) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
@@ -445,11 +446,11 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
     const int KT = d / kBK;
 
     Operand A, B;
-    operand_rows(A, w, d, (int64_t)v0 + vt * kTile, V, 0, nullptr);
-    operand_rows(B, hidden, d, tt * kTile, n_valid, 0, row_map);
+    operand_kmajor(A, wt + ((int64_t)v0 / kTile + vt) * d * kTile, kTile, 0, 0, kTile);
+    operand_kmajor(B, ht + tt * d * kTile, kTile, 0, 0, kTile);
     f32x16 acc[4][4];
     zero_acc(acc);
-    k_loop<bf16x8>(A, B, KT, lds, g, acc);
+    k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
 
     const int vloc = (int)vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // chunk-local row of (mi=0, r=0)
     const int vbase = v0 + vloc;
@@ -468,7 +469,7 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                val[mi][r] = -__builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e, off));
+                val[mi][r] = -__builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e * kInvLogitScale, off));
         const int slot = acc_slot_of(y - vbase);
         if (__any(slot >= 0)) {
 #pragma unroll
@@ -663,6 +664,47 @@ __global__ __launch_bounds__(256) void dw_onehot_kernel(const LossHeader* __rest
 }
 
 // ------------------------------------------------------------------------------------------
+// fp16 transposed operand copies for the logits contraction (once per call), so that it too reads
+// k-major tiles (512 contiguous bytes per k-row instead of 64):
+//   Wt[v/256][k][v%256] = kWScale W[v][k]            (zero for v >= V up to the end of the last tile)
+//   Ht[p/256][k][p%256] = kHScale H[row_map[p]][k]   (zero for p >= N up to the end of the last tile)
+// Blocked by 256-column tile, so that the k-tile a workgroup streams (32 k-rows x 512 B) is one
+// contiguous 16 KiB run and a whole tile column is one contiguous d x 512 B region.
+// bf16 -> fp16 is exact while the scaled value stays in fp16's normal range; the scales keep
+// |W| in [2.4e-7, 255] and |h| in [1e-3, 1e6] there (smaller values lose bits that cannot matter).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_kernel(const LossHeader* __restrict__ hdr,
+                                                        const int32_t* __restrict__ gather,
+                                                        const uint16_t* __restrict__ src, int64_t rows,
+                                                        int d, int64_t rows_out, int token_rows, float scale,
+                                                        _Float16* __restrict__ dst) {
+    __shared__ _Float16 tile[64][66];
+    int64_t nrows = rows, fill_to = rows_out;
+    if (token_rows) {
+        nrows = hdr->n_valid;
+        fill_to = (nrows + kTile - 1) / kTile * kTile;
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * 64;
+    const int k0 = blockIdx.y * 64;
+    if (r0 >= fill_to) return;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int64_t r = r0 + rr;
+        float x = 0.0f;
+        if (r < nrows && k0 + tx < d) {
+            const int64_t srow = gather ? (int64_t)gather[r] : r;
+            x = __uint_as_float((uint32_t)src[srow * d + k0 + tx] << 16) * scale;
+        }
+        tile[rr][tx] = (_Float16)x;
+    }
+    __syncthreads();
+    for (int kk = ty; kk < 64; kk += 4) {
+        const int64_t r = r0 + tx;
+        if (k0 + kk < d && r < rows_out) dst[((r / kTile) * d + (k0 + kk)) * kTile + r % kTile] = tile[tx][kk];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // fp16 operand copies (once per call):
 //   W16[v][k] = kWScale W[v][k]           (zero rows for v >= V; exact: bf16 has fewer significand bits)
 //   H16[p][k] = s g_p H[row_map[p]][k]    (zero rows for p >= N up to the end of the last token tile;
@@ -713,19 +755,29 @@ pods_status reserve(const void* kernel, const char* what) {
 
 pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
     unsigned char* ws = a.workspace;
+    auto* hdr = reinterpret_cast<const LossHeader*>(ws + p.off_hdr);
+    auto* row_map = reinterpret_cast<const int32_t*>(ws + p.off_rowmap);
+    auto* wt = reinterpret_cast<_Float16*>(ws + p.off_wtt);
+    auto* ht = reinterpret_cast<_Float16*>(ws + p.off_htt);
     pods_status st = reserve(reinterpret_cast<const void*>(fwd_kernel), "token loss forward");
     if (st != PODS_OK) return st;
+    const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
+    PODS_LAUNCH("transpose W", a.stream, transpose_kernel, dim3((unsigned)(p.vld_t / 64), dtiles64), dim3(256), 0,
+                a.stream, hdr, nullptr, static_cast<const uint16_t*>(a.w_lm), (int64_t)a.V, a.d, p.vld_t, 0,
+                kWScale, wt);
+    if ((st = check_launch("transpose W")) != PODS_OK) return st;
+    PODS_LAUNCH("transpose H", a.stream, transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
+                a.stream, hdr, row_map, static_cast<const uint16_t*>(a.hidden), (int64_t)0, a.d, p.ncap_ld, 1,
+                kHScale, ht);
+    if ((st = check_launch("transpose H")) != PODS_OK) return st;
     const int64_t ntt = p.ncap_ld / kTile;
     const int64_t groups = (ntt + 3) / 4;                                // 4 token tiles each
     const int64_t grid = (groups + kXcds - 1) / kXcds * kXcds * 32;
     PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)grid), dim3(256), kLdsBytes, a.stream,
-                       reinterpret_cast<const LossHeader*>(ws + p.off_hdr),
-                       reinterpret_cast<const int32_t*>(ws + p.off_rowmap),
-                       reinterpret_cast<const int32_t*>(ws + p.off_tok),
-                       static_cast<const uint16_t*>(a.hidden), static_cast<const uint16_t*>(a.w_lm),
-                       a.d, a.V, p.ncap_ld, reinterpret_cast<float*>(ws + p.off_pmax),
-                       reinterpret_cast<float*>(ws + p.off_psum),
-                       reinterpret_cast<float*>(ws + p.off_zy));
+                hdr, reinterpret_cast<const int32_t*>(ws + p.off_tok), reinterpret_cast<const uint16_t*>(ht),
+                reinterpret_cast<const uint16_t*>(wt), a.d, a.V, p.ncap_ld,
+                reinterpret_cast<float*>(ws + p.off_pmax), reinterpret_cast<float*>(ws + p.off_psum),
+                reinterpret_cast<float*>(ws + p.off_zy));
     return check_launch("token loss forward");
 }
 
@@ -740,6 +792,8 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
     auto* w16 = reinterpret_cast<_Float16*>(ws + p.off_wt);
     auto* h16 = reinterpret_cast<_Float16*>(ws + p.off_ht);
     auto* dz = reinterpret_cast<_Float16*>(ws + p.off_dz);
+    auto* wt = reinterpret_cast<const uint16_t*>(ws + p.off_wtt);
+    auto* ht = reinterpret_cast<const uint16_t*>(ws + p.off_htt);
     const auto* hidden = static_cast<const uint16_t*>(a.hidden);
     const auto* w = static_cast<const uint16_t*>(a.w_lm);
     pods_status st;
@@ -766,7 +820,7 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
         const int v0 = c * p.vc;
         if (v0 >= a.V) break;
         PODS_LAUNCH("token loss recompute", a.stream, recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
-                           kLdsBytes, a.stream, hdr, row_map, tok, lse, hidden, w, a.d, a.V, v0, p.vc, dz);
+                           kLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, dz);
         if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
                            a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
