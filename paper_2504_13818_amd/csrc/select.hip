@@ -4,8 +4,10 @@
 // Each lane holds KPL consecutive elements of the group as 64-bit sort keys.  A key is the
 // order-preserving integer image of the float32 reward followed by the element's index, laid
 // into the mantissa of a double in [2, 4): for such doubles floating-point order equals integer
-// order, so a compare-exchange is one v_min_f64 and one v_max_f64.  The index in the low bits
-// makes every key distinct and gives the (reward, index) order the tie rule asks for.
+// order, so an in-lane compare-exchange is one v_min_f64 and one v_max_f64 and a cross-lane one is
+// one v_cmp_lt_f64 and two selects.  The index in the low bits makes every key distinct and gives
+// the (reward, index) order the tie rule asks for.  Partner values travel by DPP moves where the
+// lane pattern allows, else through the LDS crossbar (ds_swizzle / ds_bpermute).
 // A bitonic network sorts the 64*KPL keys in registers; the sorted rewards and indices are staged
 // in LDS; prefix sums of r and r^2 over the m lowest and running sums over the k highest are
 // scanned in double precision; one candidate split k per lane is scored as m*Q - S^2 (m^2 times
@@ -45,6 +47,32 @@ __device__ __forceinline__ void cmp_exchange(double& lo, double& hi) {
     hi = b;
 }
 
+// Value of `x` held by lane (lane ^ LM).  Masks that a DPP modifier can express (1, 2, 3 within a
+// quad, 7 and 15 as half-row / row mirrors) cost one VALU move; other masks below 32 go through the
+// LDS crossbar without touching LDS memory (ds_swizzle, bit mode); masks that cross the two
+// 32-lane halves use ds_bpermute with the partner's lane index.
+template <int LM>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x, int lane) {
+    if constexpr (LM == 1) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);
+    else if constexpr (LM == 2) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true);
+    else if constexpr (LM == 3) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x1B, 0xF, 0xF, true);
+    else if constexpr (LM == 7) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x141, 0xF, 0xF, true);
+    else if constexpr (LM == 15) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x140, 0xF, 0xF, true);
+    else if constexpr (LM < 32) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x1F | (LM << 10));
+    else return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ LM) << 2, (int)x);
+}
+template <int LM>
+__device__ __forceinline__ double lane_xor(double x, int lane) {
+    const uint32_t lo = lane_xor<LM>((uint32_t)__double2loint(x), lane);
+    const uint32_t hi = lane_xor<LM>((uint32_t)__double2hiint(x), lane);
+    return __hiloint2double((int)hi, (int)lo);
+}
+
+// Keys are pairwise distinct, so "mine < other" decides; the lower lane of a pair keeps the smaller.
+__device__ __forceinline__ double keep(double mine, double other, bool lower) {
+    return ((mine < other) == lower) ? mine : other;
+}
+
 // First step of a bitonic merge of blocks of `SIZE`: element e meets e ^ (SIZE-1).
 template <int KPL, int SIZE>
 __device__ __forceinline__ void stage_mirror(double (&key)[KPL], int lane) {
@@ -59,10 +87,9 @@ __device__ __forceinline__ void stage_mirror(double (&key)[KPL], int lane) {
         const bool lower = (lane & ((LM + 1) >> 1)) == 0;
         double other[KPL];
 #pragma unroll
-        for (int j = 0; j < KPL; ++j) other[j] = __shfl_xor(key[KPL - 1 - j], LM, kWave);
+        for (int j = 0; j < KPL; ++j) other[j] = lane_xor<LM>(key[KPL - 1 - j], lane);
 #pragma unroll
-        for (int j = 0; j < KPL; ++j)
-            key[j] = lower ? fmin(key[j], other[j]) : fmax(key[j], other[j]);
+        for (int j = 0; j < KPL; ++j) key[j] = keep(key[j], other[j], lower);
     }
 }
 
@@ -79,10 +106,7 @@ __device__ __forceinline__ void stage_xor(double (&key)[KPL], int lane) {
         constexpr int LM = STRIDE / KPL;
         const bool lower = (lane & LM) == 0;
 #pragma unroll
-        for (int j = 0; j < KPL; ++j) {
-            double other = __shfl_xor(key[j], LM, kWave);
-            key[j] = lower ? fmin(key[j], other) : fmax(key[j], other);
-        }
+        for (int j = 0; j < KPL; ++j) key[j] = keep(key[j], lane_xor<LM>(key[j], lane), lower);
     }
 }
 
