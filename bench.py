@@ -21,6 +21,73 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 / fp16 MFMA peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+KERNEL_SYMBOLS = {"token loss forward": "fwd_kernel", "token loss recompute": "recompute_kernel",
+                  "token loss d_hidden": "dh_kernel", "token loss d_w_lm": "dw_kernel",
+                  "pods_select": "select_kernel"}
+PROBE_BYTES = 1 << 30         # the calibration copy reads and writes this many bytes
+
+
+def source_digest():
+    """sha256 over the HIP sources: HBM-traffic counters are only quoted for the kernels they were taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2504_13818_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
+def summarize_traffic(fetch_csv, write_csv, out_path=TRAFFIC_FILE):
+    """Turn two `rocprofv3 --pmc` runs of `bench.py --traffic-probe` (FETCH_SIZE, then WRITE_SIZE; KiB per
+    dispatch) into bytes per launch for each kernel, each counter scaled by what it reads for a plain
+    copy kernel of known size."""
+    import csv
+    import collections
+
+    def load(path, counter):
+        per = collections.defaultdict(list)
+        probe = []
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != counter:
+                continue
+            name, val = r["Kernel_Name"], float(r["Counter_Value"])
+            dur = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+            for label, sym in KERNEL_SYMBOLS.items():
+                if sym in name:
+                    per[label].append(val)
+            if "MulFunctor" in name and "vectorized_elementwise_kernel" in name:
+                probe.append((dur, val))
+        probe_kib = max(probe)[1]            # the 1 GiB probe is by far the longest such kernel
+        factor = (PROBE_BYTES / 1024.0) / probe_kib
+        return {k: 1024.0 * factor * sum(v) / len(v) for k, v in per.items()}, factor, probe_kib
+
+    fetch, f_fac, f_probe = load(fetch_csv, "FETCH_SIZE")
+    write, w_fac, w_probe = load(write_csv, "WRITE_SIZE")
+    out = {"source_sha256": source_digest(),
+           "calibration": {"probe": "torch.mul(x, 1.0, out=y) on 2^28 fp32 elements: reads 1 GiB, writes 1 GiB",
+                           "fetch_factor": f_fac, "fetch_probe_kib": f_probe,
+                           "write_factor": w_fac, "write_probe_kib": w_probe},
+           "kernels": {k: {"fetch_bytes_per_launch": fetch.get(k), "write_bytes_per_launch": write.get(k)}
+                       for k in sorted(set(fetch) | set(write))}}
+    with open(out_path, "w") as f:
+        json.dump(out, f, indent=1)
+    return out
+
+
+def recorded_traffic(kernel):
+    """HBM bytes per launch (fetch + write) from profiles/traffic.json, or None when absent or stale."""
+    try:
+        t = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return None
+    if t.get("source_sha256") != source_digest():
+        return None
+    k = t.get("kernels", {}).get(kernel)
+    if not k or k.get("fetch_bytes_per_launch") is None or k.get("write_bytes_per_launch") is None:
+        return None
+    return k["fetch_bytes_per_launch"] + k["write_bytes_per_launch"]
 
 
 def current_logp_torch(torch, hidden, w, tokens, chunk=4096):
@@ -62,7 +129,7 @@ def time_selector(lib, torch, inputs, steps):
     return dict(workload="selector-stress B=65536 n=256 m=64 fp32", ms_per_launch=ms,
                 groups_per_s=B / (ms * 1e-3), launches=len(prof),
                 roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
-                              frac=gbs / PEAK_HBM_GBS, traffic=None,
+                              frac=gbs / PEAK_HBM_GBS, traffic=None,   # not taken for this kernel yet
                               bytes_per_group=bytes_per_group))
 
 
@@ -107,7 +174,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=1, choices=[1, 2, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run a 1 GiB copy kernel, the calibration for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--summarize-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: write profiles/traffic.json from two --pmc counter_collection.csv files")
     args = ap.parse_args()
+    if args.summarize_traffic:
+        print(json.dumps(summarize_traffic(*args.summarize_traffic), indent=1))
+        return
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
               "(groups and rollouts shard across GPUs without exchange; see DESIGN.md).", file=sys.stderr)
@@ -158,6 +232,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.traffic_probe:
+        px = torch.ones(PROBE_BYTES // 4, dtype=torch.float32, device=dev)
+        py = torch.empty_like(px)
+        torch.mul(px, 1.0, out=py)
+        torch.cuda.synchronize()
+        del px, py
     lib.pods_profile_enable(True)               # HIP events around every launch, on the launch stream
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -188,7 +268,7 @@ def main():
     achieved = flops_per_launch / (dk["avg_ms"] * 1e-3) / 1e12
     gpu_ms = sum(v["ms_per_step"] for v in kernels.values())
     roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                    frac=achieved / PEAK_BF16_TFLOPS, traffic=recorded_traffic(dominant),
                     flops_per_launch=flops_per_launch, avg_launch_ms=dk["avg_ms"],
                     path_executed_tflops=4 * flops_family / (gpu_ms * 1e-3) / 1e12,
                     path_executed_frac=4 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

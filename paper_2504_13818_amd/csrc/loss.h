@@ -51,8 +51,6 @@ constexpr float kWScale = 256.0f;    // fp16 weight copies hold kWScale * W
 constexpr float kHScale = 0.0625f;   // fp16 transposed hidden copy holds kHScale * h
 
 constexpr int kTile = 256;          // token / vocab / hidden tile edge of the matrix-core kernels
-constexpr int kFwdVocabSplits = 8;  // vocabulary splits of the forward pass (one per XCD slot)
-constexpr int kFwdSlotsMfma = kFwdVocabSplits * 2;  // (max, sum-exp) partials per token
 constexpr int kDefaultVocabChunk = 8192;
 
 struct LossPlan {

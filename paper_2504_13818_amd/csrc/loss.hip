@@ -10,7 +10,7 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     p.ncap = (int64_t)R * T;
     p.ncap_ld = (p.ncap + kTile - 1) / kTile * kTile;
     p.mfma = (dt == PODS_BF16) && (d % 64 == 0);
-    p.slots = p.mfma ? kFwdSlotsMfma : 1;
+    p.slots = p.mfma ? (int)(((int64_t)V + kTile - 1) / kTile) : 1;   // one partial per vocabulary tile
     p.loss_blocks = (int)ceil_div(p.ncap, 256);
     size_t off = 0;
     auto take = [&](size_t bytes) {

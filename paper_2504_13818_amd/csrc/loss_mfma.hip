@@ -322,7 +322,10 @@ __device__ __forceinline__ int acc_slot_of(int rel) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Forward: per token, (max, sum exp) over this workgroup's share of the vocabulary, and z_y.
+// Forward: one workgroup per (token tile, vocabulary tile): (max, sum exp) of its 256 logits per
+// token, one partial per vocabulary tile, merged later by the surrogate kernel; and z_y.
+// One tile per workgroup (rather than a workgroup walking many vocabulary tiles) keeps the 32
+// workgroups of an XCD in step, which is what lets them share operand tiles in the 4 MiB L2.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restrict__ hdr,
                                                      const int32_t* __restrict__ tok,
@@ -333,97 +336,90 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
                                                      float* __restrict__ zy) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
-    // ids congruent mod 8 (one XCD): 4 token tiles x 8 vocabulary splits
-    const int64_t bid = blockIdx.x;
-    const int64_t xcd = bid % kXcds, q = bid / kXcds;
-    const int64_t tt = ((q / 32) * kXcds + xcd) * 4 + (q % 32) / kFwdVocabSplits;
-    const int vs = (int)(q % kFwdVocabSplits);
-    if (tt * kTile >= n_valid) return;
-    const LaneGeom g = lane_geom();
+    const int64_t ntt = (n_valid + kTile - 1) / kTile;
     const int nvt = (V + kTile - 1) / kTile;
+    int64_t tt, vt;
+    if (!decode_tile(blockIdx.x, ntt, nvt, tt, vt)) return;
+    const LaneGeom g = lane_geom();
     const int KT = d / kBK;
 
     Operand A, B;
+    operand_kmajor(A, wt + vt * d * kTile, kTile, 0, 0, kTile);
     operand_kmajor(B, ht + tt * d * kTile, kTile, 0, 0, kTile);
+    f32x16 acc[4][4];
+    zero_acc(acc);
+    k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
 
-    int y[4];
-    float M[4], L[4];
+    const int vbase = (int)vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // row of (mi=0, r=0)
+    if ((int)vt * kTile + kTile > V) {  // last, partial vocabulary tile: rows >= V do not exist
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int v = vbase + mi * 32 + 8 * (r >> 2) + (r & 3);
+                if (v >= V) {
+#pragma unroll
+                    for (int ni = 0; ni < 4; ++ni) acc[mi][ni][r] = -__builtin_huge_valf();
+                }
+            }
+    }
+    float* red = reinterpret_cast<float*>(lds);   // [2 wn][128 tokens][2]: wm = 1 hands its partials to wm = 0
+    __builtin_amdgcn_s_barrier();                 // every wave has left the ring
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
-        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
-        y[ni] = (p < n_valid) ? tok[p] : -1;
-        M[ni] = -__builtin_huge_valf();
-        L[ni] = 0.0f;
-    }
-
-    f32x16 acc[4][4];
-    for (int vt = vs; vt < nvt; vt += kFwdVocabSplits) {
-        zero_acc(acc);
-        operand_kmajor(A, wt + (int64_t)vt * d * kTile, kTile, 0, 0, kTile);
-        k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
-        advance(B, -(int64_t)(KT - 1) * B.step);   // back to the first k-tile
-
-        const int vbase = vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // row of (mi=0, r=0)
-        if (vt * kTile + kTile > V) {  // last, partial vocabulary tile: rows >= V do not exist
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int v = vbase + mi * 32 + 8 * (r >> 2) + (r & 3);
-                    if (v >= V) {
-#pragma unroll
-                        for (int ni = 0; ni < 4; ++ni) acc[mi][ni][r] = -__builtin_huge_valf();
-                    }
-                }
-        }
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            // z_y lives in exactly one lane of one wave of one vocabulary tile
-            const int slot = acc_slot_of(y[ni] - vbase);
-            if (__any(slot >= 0)) {
-                float val = 0.0f;
-#pragma unroll
-                for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (slot == mi * 16 + r) val = acc[mi][ni][r];
-                if (slot >= 0) zy[tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31)] = val * kInvLogitScale;
-            }
-            float m = acc[0][ni][0];
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[mi][ni][r]);
-            const float Mn = fmaxf(M[ni], m * kInvLogitScale);   // accumulators hold kLogitScale * z
-            const float Ms = (Mn == -__builtin_huge_valf()) ? 0.0f : Mn;
-            const float off = -Ms * kLog2e;
-            float s = 0.0f;
+        const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
+        const int64_t p = tt * kTile + tloc;
+        const int y = (p < n_valid) ? tok[p] : -1;
+        // z_y lives in exactly one lane of one wave of one vocabulary tile
+        const int slot = acc_slot_of(y - vbase);
+        if (__any(slot >= 0)) {
+            float val = 0.0f;
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    s += __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e * kInvLogitScale, off));
-            L[ni] = L[ni] * __builtin_amdgcn_exp2f(fmaf(M[ni], kLog2e, off)) + s;
-            M[ni] = Mn;
+                    if (slot == mi * 16 + r) val = acc[mi][ni][r];
+            if (slot >= 0) zy[p] = val * kInvLogitScale;
         }
-    }
-
-    // lanes l and l^32 hold the same tokens over different vocabulary rows
-    const int slot_id = vs * 2 + g.wm;
+        float m = acc[0][ni][0];
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        const float Mo = __shfl_xor(M[ni], 32, 64);
-        const float Lo = __shfl_xor(L[ni], 32, 64);
-        const float Mn = fmaxf(M[ni], Mo);
-        float Lt = 0.0f;
-        if (Mn > -__builtin_huge_valf()) {
-            Lt = L[ni] * __builtin_amdgcn_exp2f((M[ni] - Mn) * kLog2e) +
-                 Lo * __builtin_amdgcn_exp2f((Mo - Mn) * kLog2e);
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[mi][ni][r]);
+        m = fmaxf(m, __shfl_xor(m, 32, 64));          // lanes l and l^32: same token, other rows
+        const float M = m * kInvLogitScale;           // accumulators hold kLogitScale * z
+        const float Ms = (M == -__builtin_huge_valf()) ? 0.0f : M;
+        const float off = -Ms * kLog2e;
+        float sum = 0.0f;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                sum += __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e * kInvLogitScale, off));
+        sum += __shfl_xor(sum, 32, 64);
+        if (g.wm == 1 && g.lane < 32) {
+            red[tloc * 2] = M;
+            red[tloc * 2 + 1] = sum;
         }
-        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
-        if (g.lane < 32 && p < n_valid) {
-            pmax[slot_id * slot_stride + p] = Mn;
-            psum[slot_id * slot_stride + p] = Lt;
+        acc[0][ni][0] = M;     // keep the pair for the merge below
+        acc[0][ni][1] = sum;
+    }
+    __syncthreads();
+    if (g.wm == 0 && g.lane < 32) {
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            const int tloc = g.wn * 128 + ni * 32 + g.lane;
+            const int64_t p = tt * kTile + tloc;
+            const float M0 = acc[0][ni][0], S0 = acc[0][ni][1];
+            const float M1 = red[tloc * 2], S1 = red[tloc * 2 + 1];
+            const float Mn = fmaxf(M0, M1);
+            float St = 0.0f;
+            if (Mn > -__builtin_huge_valf())
+                St = S0 * __builtin_amdgcn_exp2f((M0 - Mn) * kLog2e) + S1 * __builtin_amdgcn_exp2f((M1 - Mn) * kLog2e);
+            if (p < n_valid) {
+                pmax[vt * slot_stride + p] = Mn;
+                psum[vt * slot_stride + p] = St;
+            }
         }
     }
 }
@@ -771,11 +767,10 @@ pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
                 kHScale, ht);
     if ((st = check_launch("transpose H")) != PODS_OK) return st;
     const int64_t ntt = p.ncap_ld / kTile;
-    const int64_t groups = (ntt + 3) / 4;                                // 4 token tiles each
-    const int64_t grid = (groups + kXcds - 1) / kXcds * kXcds * 32;
-    PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)grid), dim3(256), kLdsBytes, a.stream,
-                hdr, reinterpret_cast<const int32_t*>(ws + p.off_tok), reinterpret_cast<const uint16_t*>(ht),
-                reinterpret_cast<const uint16_t*>(wt), a.d, a.V, p.ncap_ld,
+    const int64_t nvt = p.vld_t / kTile;
+    PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nvt)), dim3(256),
+                kLdsBytes, a.stream, hdr, reinterpret_cast<const int32_t*>(ws + p.off_tok),
+                reinterpret_cast<const uint16_t*>(ht), reinterpret_cast<const uint16_t*>(wt), a.d, a.V, p.ncap_ld,
                 reinterpret_cast<float*>(ws + p.off_pmax), reinterpret_cast<float*>(ws + p.off_psum),
                 reinterpret_cast<float*>(ws + p.off_zy));
     return check_launch("token loss forward");
