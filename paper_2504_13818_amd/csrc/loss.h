@@ -60,6 +60,7 @@ struct LossPlan {
     int slots;        // forward partial slots per token
     int vc;           // vocabulary chunk of the backward pass (multiple of kTile); 0 on the plain path
     int nchunks;
+    int64_t ldq;      // row pitch of q in elements: vc plus one tile, so rows do not sit a power of two apart
     int64_t vld;      // rows of the fp16 weight copy = nchunks * vc (zero past V)
     int64_t vld_t;    // columns of the transposed fp16 weight copy = V rounded up to kTile
     int loss_blocks;

@@ -30,7 +30,7 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     p.off_psum = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
     p.off_losspart = take(sizeof(double) * (size_t)p.loss_blocks);
     if (!p.mfma) {
-        p.vc = 0; p.nchunks = 0; p.vld = 0; p.vld_t = 0;
+        p.vc = 0; p.nchunks = 0; p.ldq = 0; p.vld = 0; p.vld_t = 0;
         p.off_wtt = p.off_htt = p.off_wt = p.off_ht = p.off_dz = off;
         p.total = off;
         return p;
@@ -48,7 +48,8 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
         q.vld = (int64_t)q.nchunks * vc;
         q.off_wt = tk(2 * (size_t)d * (size_t)q.vld);
         q.off_ht = tk(2 * (size_t)d * (size_t)p.ncap_ld);
-        q.off_dz = tk(2 * (size_t)p.ncap_ld * (size_t)vc);
+        q.ldq = vc + kTile;
+        q.off_dz = tk(2 * (size_t)p.ncap_ld * (size_t)q.ldq);
         q.total = o;
     };
     int vc;

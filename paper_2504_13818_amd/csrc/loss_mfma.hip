@@ -431,13 +431,14 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 __global__ __launch_bounds__(256, 1) void recompute_kernel(
     const LossHeader* __restrict__ hdr, const int32_t* __restrict__ tok,
     const float* __restrict__ lse, const uint16_t* __restrict__ ht,
-    const uint16_t* __restrict__ wt, int d, int V, int v0, int vc,
+    const uint16_t* __restrict__ wt, int d, int V, int v0, int vc, int64_t ldq,
     _Float16* __restrict__ q) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
     int64_t tt, vt;
     if (!decode_tile(blockIdx.x, ntt, vc / kTile, tt, vt)) return;
+    if ((int64_t)v0 + vt * kTile >= V) return;   // past the vocabulary: the gradient kernels stop there too
     const LaneGeom g = lane_geom();
     const int KT = d / kBK;
 
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
 #pragma unroll
                 for (int c = 0; c < 4; ++c) pk[c] = (_Float16)val[mi][b * 4 + c];
                 const int vl = vloc + mi * 32 + 8 * b;
-                *reinterpret_cast<f16x4*>(q + p * vc + vl) = pk;
+                *reinterpret_cast<f16x4*>(q + p * ldq + vl) = pk;
             }
     }
 }
@@ -502,8 +503,8 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
                                                     const int32_t* __restrict__ row_map,
                                                     const float* __restrict__ gvec,
                                                     const uint16_t* __restrict__ w16,
-                                                    const uint16_t* __restrict__ q, int d, int v0,
-                                                    int vc, float* __restrict__ d_hidden) {
+                                                    const uint16_t* __restrict__ q, int64_t ldq, int d,
+                                                    int V, int v0, int vc, float* __restrict__ d_hidden) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
@@ -514,10 +515,11 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     Operand A, B;
     operand_kmajor(A, w16, d, v0, kt0 * kTile, d);   // rows v >= V of W16 are zero
     // every row of the last token tile was written by the recompute step (zeros past N)
-    operand_rows(B, q, vc, tt * kTile, ntt * kTile, 0, nullptr);
+    operand_rows(B, q, ldq, tt * kTile, ntt * kTile, 0, nullptr);
     f32x16 acc[4][4];
     zero_acc(acc);
-    k_loop<f16x8, true, false>(A, B, vc / kBK, lds, g, acc);
+    const int vwidth = min(vc, (V - v0 + kTile - 1) / kTile * kTile);   // whole tiles that hold vocabulary
+    k_loop<f16x8, true, false>(A, B, vwidth / kBK, lds, g, acc);
 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
@@ -546,7 +548,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict__ hdr,
                                                     const uint16_t* __restrict__ h16,
-                                                    const uint16_t* __restrict__ q,
+                                                    const uint16_t* __restrict__ q, int64_t ldq,
                                                     int d, int V, int v0, int vc,
                                                     float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -559,7 +561,7 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
     Operand A, B;
     // token rows past N (up to the end of the last token tile) are zero in both operands
     operand_kmajor(A, h16, d, 0, kt0 * kTile, d);
-    operand_kmajor(B, q, vc, 0, vt * kTile, vc);
+    operand_kmajor(B, q, ldq, 0, vt * kTile, vc);
     f32x16 acc[4][4];
     zero_acc(acc);
     const int KT = (n_valid + kBK - 1) / kBK;
@@ -815,15 +817,15 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
         const int v0 = c * p.vc;
         if (v0 >= a.V) break;
         PODS_LAUNCH("token loss recompute", a.stream, recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
-                           kLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, dz);
+                           kLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, p.ldq, dz);
         if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
                            a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
-                           reinterpret_cast<const uint16_t*>(dz), a.d, v0, p.vc, a.d_hidden);
+                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
                            kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(h16),
-                           reinterpret_cast<const uint16_t*>(dz), a.d, a.V, v0, p.vc, a.d_w_lm);
+                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, a.d_w_lm);
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
     }
     PODS_LAUNCH("token loss d_w_lm (y logit)", a.stream, dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,
