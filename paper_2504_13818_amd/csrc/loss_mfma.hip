@@ -265,8 +265,16 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
             }
             __builtin_amdgcn_sched_barrier(0);
             { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
-            if (i < 4) fa[1][i] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, i, 1);
-            else fb[1][i - 4] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, i - 4, 1);
+            // all of F1 is requested in the first four slots (in the order phase 1 consumes it), so that
+            // the wait before the barrier finds it long since delivered
+            if (i == 0) { fa[1][0] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 0, 1);
+                          fb[1][0] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 0, 1); }
+            if (i == 1) { fb[1][1] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 1, 1);
+                          fb[1][2] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 2, 1); }
+            if (i == 2) { fb[1][3] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 3, 1);
+                          fa[1][1] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 1, 1); }
+            if (i == 3) { fa[1][2] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 2, 1);
+                          fa[1][3] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 3, 1); }
             __builtin_amdgcn_sched_barrier(0);
         }
         wait_vmcnt<8 * (kDist - 1)>();   // loads return in order: everything but the newest kDist-1 tiles is in LDS
@@ -277,8 +285,14 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
         for (int i = 0; i < 8; ++i) {
             { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
             { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
-            if (i < 4) fa[0][i] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, i, 0);
-            else fb[0][i - 4] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, i - 4, 0);
+            if (i == 0) { fa[0][0] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 0, 0);
+                          fb[0][0] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 0, 0); }
+            if (i == 1) { fb[0][1] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 1, 0);
+                          fb[0][2] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 2, 0); }
+            if (i == 2) { fb[0][3] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 3, 0);
+                          fa[0][1] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 1, 0); }
+            if (i == 3) { fa[0][2] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 2, 0);
+                          fa[0][3] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 3, 0); }
             __builtin_amdgcn_sched_barrier(0);
         }
         st = stn;
