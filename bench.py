@@ -28,14 +28,17 @@ KERNEL_SYMBOLS = {"token loss forward": "fwd_kernel", "token loss recompute": "r
 PROBE_BYTES = 1 << 30         # the calibration copy reads and writes this many bytes
 
 
-def source_digest():
-    """sha256 over the HIP sources: HBM-traffic counters are only quoted for the kernels they were taken on."""
+LOSS_SOURCES = ("common.h", "loss.h", "loss.hip", "loss_mfma.hip")
+
+
+def source_digest(names=LOSS_SOURCES):
+    """sha256 over the token-loss HIP sources: HBM-traffic counters are only quoted for the kernels
+    they were taken on."""
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2504_13818_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".h")):
-            h.update(open(os.path.join(csrc, name), "rb").read())
+    for name in names:
+        h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()
 
 

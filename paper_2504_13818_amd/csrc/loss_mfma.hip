@@ -365,41 +365,43 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
     k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
 
     const int vbase = (int)vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // row of (mi=0, r=0)
-    if ((int)vt * kTile + kTile > V) {  // last, partial vocabulary tile: rows >= V do not exist
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int v = vbase + mi * 32 + 8 * (r >> 2) + (r & 3);
-                if (v >= V) {
-#pragma unroll
-                    for (int ni = 0; ni < 4; ++ni) acc[mi][ni][r] = -__builtin_huge_valf();
-                }
-            }
-    }
-    float* red = reinterpret_cast<float*>(lds);   // [2 wn][128 tokens][2]: wm = 1 hands its partials to wm = 0
+    const bool partial = (int)vt * kTile + kTile > V;   // last vocabulary tile: rows >= V do not exist
+    float* red = reinterpret_cast<float*>(lds);   // [256 tokens][2]: wm = 1 hands its partials to wm = 0
+    float Mv[4], Sv[4];
     __builtin_amdgcn_s_barrier();                 // every wave has left the ring
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
         const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
         const int64_t p = tt * kTile + tloc;
         const int y = (p < n_valid) ? tok[p] : -1;
-        // z_y lives in exactly one lane of one wave of one vocabulary tile
-        const int slot = acc_slot_of(y - vbase);
-        if (__any(slot >= 0)) {
-            float val = 0.0f;
+        float val[4][16];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) val[mi][r] = acc[mi][ni][r];
+        if (partial) {
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (slot == mi * 16 + r) val = acc[mi][ni][r];
-            if (slot >= 0) zy[p] = val * kInvLogitScale;
+                    if (vbase + mi * 32 + 8 * (r >> 2) + (r & 3) >= V) val[mi][r] = -__builtin_huge_valf();
         }
-        float m = acc[0][ni][0];
+        // z_y lives in exactly one lane of one wave of one vocabulary tile
+        const int slot = acc_slot_of(y - vbase);
+        if (__any(slot >= 0)) {
+            float zv = 0.0f;
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (slot == mi * 16 + r) zv = val[mi][r];
+            if (slot >= 0) zy[p] = zv * kInvLogitScale;
+        }
+        float m = val[0][0];
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[mi][ni][r]);
+            for (int r = 0; r < 16; ++r) m = fmaxf(m, val[mi][r]);
         m = fmaxf(m, __shfl_xor(m, 32, 64));          // lanes l and l^32: same token, other rows
         const float M = m * kInvLogitScale;           // accumulators hold kLogitScale * z
         const float Ms = (M == -__builtin_huge_valf()) ? 0.0f : M;
@@ -409,14 +411,15 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                sum += __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e * kInvLogitScale, off));
+                sum += __builtin_amdgcn_exp2f(fmaf(val[mi][r], kLog2e * kInvLogitScale, off));
         sum += __shfl_xor(sum, 32, 64);
         if (g.wm == 1 && g.lane < 32) {
             red[tloc * 2] = M;
             red[tloc * 2 + 1] = sum;
         }
-        acc[0][ni][0] = M;     // keep the pair for the merge below
-        acc[0][ni][1] = sum;
+        Mv[ni] = M;
+        Sv[ni] = sum;
+        __builtin_amdgcn_sched_barrier(0);   // one token column at a time: keeps the accumulator copies few
     }
     __syncthreads();
     if (g.wm == 0 && g.lane < 32) {
@@ -424,12 +427,11 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
         for (int ni = 0; ni < 4; ++ni) {
             const int tloc = g.wn * 128 + ni * 32 + g.lane;
             const int64_t p = tt * kTile + tloc;
-            const float M0 = acc[0][ni][0], S0 = acc[0][ni][1];
             const float M1 = red[tloc * 2], S1 = red[tloc * 2 + 1];
-            const float Mn = fmaxf(M0, M1);
+            const float Mn = fmaxf(Mv[ni], M1);
             float St = 0.0f;
             if (Mn > -__builtin_huge_valf())
-                St = S0 * __builtin_amdgcn_exp2f((M0 - Mn) * kLog2e) + S1 * __builtin_amdgcn_exp2f((M1 - Mn) * kLog2e);
+                St = Sv[ni] * __builtin_amdgcn_exp2f((Mv[ni] - Mn) * kLog2e) + S1 * __builtin_amdgcn_exp2f((M1 - Mn) * kLog2e);
             if (p < n_valid) {
                 pmax[vt * slot_stride + p] = Mn;
                 psum[vt * slot_stride + p] = St;
