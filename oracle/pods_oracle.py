@@ -16,7 +16,12 @@ What each function follows:
                                subsets, exact rationals.
 * ``select_prefix``            Theorem 1's O(n log n) evaluation: prefix sums of r and r^2,
                                Var = E[x^2] - E[x]^2, O(1) per k; float64.
+* ``downsample_maxr`` / ``downsample_perc`` / ``downsample_rand``
+                               the other rules of Sec. 3.2 (max-reward, percentile, random), each
+                               written as its definition on the (reward, index) sorted order.
 * ``advantage``                a_{S,i} = (r_i - mu_S) / sigma_S over the kept rollouts (Sec. 3.2).
+* ``advantage_before``         the "Before" variant of App. "On Advantage Normalization": mean and
+                               standard deviation from all n rollouts of the group.
 * ``grpo_token_loss``          L_PODS (Sec. 3.2) with the policy's last layer written out
                                (logits = hidden . W_lm^T, softmax over the vocabulary), returned
                                as loss = -L_PODS with its analytic gradient w.r.t. hidden and W_lm.
@@ -120,6 +125,56 @@ def select_batch(rewards: np.ndarray, m: int, exact: bool = False):
 
 
 # --------------------------------------------------------------------------------------------
+# Stage 1, other rules (Sec. 3.2: random, percentile and max-reward down-sampling)
+# --------------------------------------------------------------------------------------------
+
+def downsample_maxr(r, m: int) -> list[int]:
+    """D_maxr: the m highest rewards.  Returned in ascending (reward, index) order, so among equal
+    rewards at the cut the highest indices are the ones kept."""
+    n = len(r)
+    assert 0 < m <= n
+    return stable_argsort(r)[n - m:]
+
+
+def downsample_perc(r, m: int) -> list[int]:
+    """D_perc: the (j - 0.5)/m quantiles of the group's rewards, j = 1..m.
+
+    The paper does not say which order statistic realises a quantile q.  Reading taken: position
+    floor(q n) of the ascending (reward, index) order (0-based), i.e. floor((2j - 1) n / (2m)),
+    in integer arithmetic.  The m positions are distinct whenever m <= n."""
+    n = len(r)
+    assert 0 < m <= n
+    ind = stable_argsort(r)
+    return [ind[((2 * j - 1) * n) // (2 * m)] for j in range(1, m + 1)]
+
+
+def downsample_rand(keys, m: int) -> list[int]:
+    """D_rand: m indices uniformly without replacement.  The randomness is an input: one key per
+    rollout (independent uniform 32-bit integers); the m smallest keys are kept, ties by index,
+    returned in ascending (key, index) order.  With exchangeable keys every m-subset is equally
+    likely.  The rewards play no part."""
+    n = len(keys)
+    assert 0 < m <= n
+    return sorted(range(n), key=lambda i: (int(keys[i]), i))[:m]
+
+
+def downsample_batch(rewards: np.ndarray, m: int, rule: str, keys: np.ndarray | None = None) -> np.ndarray:
+    """Row-wise application of one of the rules above -> sel_idx[B, m] int32."""
+    B = rewards.shape[0]
+    out = np.zeros((B, m), dtype=np.int32)
+    for b in range(B):
+        if rule == "maxr":
+            out[b] = downsample_maxr(rewards[b], m)
+        elif rule == "perc":
+            out[b] = downsample_perc(rewards[b], m)
+        elif rule == "rand":
+            out[b] = downsample_rand(keys[b], m)
+        else:
+            raise ValueError(rule)
+    return out
+
+
+# --------------------------------------------------------------------------------------------
 # Stage 2: advantages over the kept rollouts (Sec. 3.2)
 # --------------------------------------------------------------------------------------------
 
@@ -137,6 +192,23 @@ def advantage(rewards: np.ndarray, sel_idx: np.ndarray, std_eps: float = 0.0) ->
         mu = x.sum() / m
         sigma = np.sqrt(((x - mu) ** 2).sum() / m)
         out[b] = (x - mu) / (sigma + std_eps)
+    return out
+
+
+def advantage_before(rewards: np.ndarray, sel_idx: np.ndarray, std_eps: float = 0.0) -> np.ndarray:
+    """ "Before" normalisation (App. "On Advantage Normalization"): the statistics come from all n
+    rollouts of the group, a_i = (r_i - mu_all) / (sigma_all + std_eps) for the kept i; float64.
+    A group whose n rewards are all equal gets 0."""
+    B, m = sel_idx.shape
+    n = rewards.shape[1]
+    out = np.zeros((B, m), dtype=np.float64)
+    for b in range(B):
+        x = rewards[b].astype(np.float64)
+        if x.max() == x.min():
+            continue
+        mu = x.sum() / n
+        sigma = np.sqrt(((x - mu) ** 2).sum() / n)
+        out[b] = (x[sel_idx[b]] - mu) / (sigma + std_eps)
     return out
 
 
