@@ -6,7 +6,11 @@
  *
  *   pods_select               max-variance down-sampling, batched over prompt groups
  *                             (Sec. 3.3: definition, Lemma 3.1, Algorithm 2, Theorem 1)
+ *   pods_downsample           the same selection step under any of the paper's rules: max-variance,
+ *                             max-reward, percentile, random (Sec. 3.2)
  *   pods_advantage            group-normalised advantages over the kept rollouts (Sec. 3.2)
+ *   pods_advantage_before     the "Before" variant: statistics from all n rollouts of the group
+ *                             (App. "On Advantage Normalization")
  *   grpo_token_loss_fwd_bwd   the GRPO-PODS objective L_PODS(theta, S) (Sec. 3.2, and L_GRPO in
  *                             Sec. 3.1) taken through the policy's last layer: the lm_head
  *                             projection, log-softmax, importance ratio, clipped surrogate, and
@@ -65,6 +69,37 @@ typedef enum { PODS_F32 = 0, PODS_BF16 = 1 } pods_dtype;
 pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m,
                         int32_t* sel_idx, int32_t* sel_k, void* stream);
 
+/* The down-sampling step of the PODS framework (Algorithm 1, step 3) under a chosen rule
+ * (Sec. 3.2 for the first three, Sec. 3.3 for max-variance).  All rules read positions of the
+ * group's order ascending by (key, index), where the key is the reward (-0.0 equal to +0.0) or,
+ * for PODS_RULE_RAND, the caller's random key:
+ *
+ *   PODS_RULE_MAXVAR  exactly pods_select.
+ *   PODS_RULE_MAXR    D_maxr, the m highest rewards: positions n-m .. n-1 (so among equal rewards at
+ *                     the cut, the highest indices are kept).  sel_k receives m.
+ *   PODS_RULE_PERC    D_perc, the (j - 1/2)/m quantiles, j = 1..m.  The paper names no order
+ *                     statistic for a quantile q; taken here as position floor(q n), i.e.
+ *                     floor((2j - 1) n / (2m)) in integers.  sel_k receives -1.
+ *   PODS_RULE_RAND    D_rand, m indices uniformly without replacement.  The library draws nothing:
+ *                     the caller passes one 32-bit key per rollout (independent uniform draws) and
+ *                     the m smallest (key, index) are kept; rewards may be NULL.  sel_k receives -1.
+ *
+ *   rewards    [B, n] float32, in (unused and may be NULL for PODS_RULE_RAND)
+ *   rand_keys  [B, n] uint32, in (PODS_RULE_RAND only; NULL otherwise)
+ *   sel_idx    [B, m] int32, out, in the order of the positions listed above
+ *   sel_k      [B]    int32, out, may be NULL
+ *   1 <= m <= n <= 4096.
+ */
+typedef enum {
+    PODS_RULE_MAXVAR = 0,
+    PODS_RULE_MAXR = 1,
+    PODS_RULE_PERC = 2,
+    PODS_RULE_RAND = 3
+} pods_rule;
+
+pods_status pods_downsample(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n,
+                            int32_t m, pods_rule rule, int32_t* sel_idx, int32_t* sel_k, void* stream);
+
 /* Advantages over the kept rollouts (Sec. 3.2): a_{S,i} = (r_i - mu_S) / (sigma_S + std_eps)
  * with mu_S, sigma_S the mean and population standard deviation of the m kept rewards, so each
  * group's advantages sum to zero.  A group whose kept rewards are all equal gets exactly 0.
@@ -76,6 +111,14 @@ pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m,
  */
 pods_status pods_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
                            int32_t m, float std_eps, float* adv, void* stream);
+
+/* "Before" normalisation (App. "On Advantage Normalization"): a_i = (r_i - mu) / (sigma + std_eps)
+ * for the kept i, with mu and the population sigma taken over all n rollouts of the group, i.e.
+ * before down-sampling; a group's kept advantages then need not sum to zero.  A group whose n
+ * rewards are all equal gets exactly 0.  Arguments as pods_advantage.
+ */
+pods_status pods_advantage_before(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
+                                  int32_t m, float std_eps, float* adv, void* stream);
 
 /* Bytes of workspace grpo_token_loss_fwd_bwd wants for these sizes (a recommendation: any
  * workspace of at least grpo_token_loss_workspace_min_bytes works, a larger one lets the

@@ -5,13 +5,14 @@ libpods_hip.so; every step of the path runs in the library's HIP kernels.  PyTor
 device memory and streams only.  There is no CPU fallback: if the library is missing or a call
 fails, an exception is raised.
 """
-from .binding import (PodsError, load, library_path, pods_select, pods_advantage,
-                      grpo_token_loss_fwd_bwd, grpo_token_loss_workspace_bytes,
+from .binding import (PodsError, load, library_path, pods_select, pods_downsample, pods_advantage,
+                      pods_advantage_before, grpo_token_loss_fwd_bwd, grpo_token_loss_workspace_bytes,
                       grpo_token_loss_workspace_min_bytes, pods_last_error, pods_profile_enable,
-                      pods_profile_read, PODS_F32, PODS_BF16, EXPORTED_SYMBOLS)
+                      pods_profile_read, PODS_F32, PODS_BF16, PODS_RULE_MAXVAR, PODS_RULE_MAXR,
+                      PODS_RULE_PERC, PODS_RULE_RAND, EXPORTED_SYMBOLS)
 
-__all__ = ["PodsError", "load", "library_path", "pods_select", "pods_advantage",
-           "grpo_token_loss_fwd_bwd", "grpo_token_loss_workspace_bytes",
+__all__ = ["PodsError", "load", "library_path", "pods_select", "pods_downsample", "pods_advantage",
+           "pods_advantage_before", "grpo_token_loss_fwd_bwd", "grpo_token_loss_workspace_bytes",
            "grpo_token_loss_workspace_min_bytes", "pods_last_error", "pods_profile_enable",
-           "pods_profile_read", "PODS_F32", "PODS_BF16",
+           "pods_profile_read", "PODS_F32", "PODS_BF16", "PODS_RULE_MAXVAR", "PODS_RULE_MAXR", "PODS_RULE_PERC", "PODS_RULE_RAND",
            "EXPORTED_SYMBOLS"]

@@ -9,7 +9,9 @@ _LIB_PATH = os.path.join(_HERE, "libpods_hip.so")
 _lib = None
 
 PODS_F32, PODS_BF16 = 0, 1
-EXPORTED_SYMBOLS = ("pods_select", "pods_advantage", "grpo_token_loss_workspace_bytes",
+PODS_RULE_MAXVAR, PODS_RULE_MAXR, PODS_RULE_PERC, PODS_RULE_RAND = 0, 1, 2, 3
+EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_advantage_before",
+                    "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
 
@@ -39,8 +41,12 @@ def load():
     lib.pods_last_error.argtypes = []
     lib.pods_select.restype = ctypes.c_int
     lib.pods_select.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
-    lib.pods_advantage.restype = ctypes.c_int
-    lib.pods_advantage.argtypes = [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp]
+    lib.pods_downsample.restype = ctypes.c_int
+    lib.pods_downsample.argtypes = [_vp, _vp, _i32, _i32, _i32, ctypes.c_int, _vp, _vp, _vp]
+    for name in ("pods_advantage", "pods_advantage_before"):
+        f = getattr(lib, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp]
     for name in ("grpo_token_loss_workspace_bytes", "grpo_token_loss_workspace_min_bytes"):
         f = getattr(lib, name)
         f.restype = _sz
@@ -113,7 +119,35 @@ def pods_select(rewards, m: int, sel_idx=None, sel_k=None, stream=None):
     return sel_idx, sel_k
 
 
-def pods_advantage(rewards, sel_idx, std_eps: float = 0.0, adv=None, stream=None):
+def pods_downsample(rewards, m: int, rule: int, rand_keys=None, sel_idx=None, sel_k=None, stream=None):
+    """rewards[B, n] float32 (device; may be None for the random rule) and, for the random rule,
+    rand_keys[B, n] uint32 or int32 (read as unsigned) -> (sel_idx[B, m] int32, sel_k[B] int32)."""
+    import torch
+    if rewards is not None:
+        _need(rewards, torch.float32, "rewards")
+    if rand_keys is not None and not (isinstance(rand_keys, torch.Tensor) and rand_keys.is_cuda and
+                                      rand_keys.is_contiguous() and
+                                      rand_keys.dtype in (torch.int32, torch.uint32)):
+        raise TypeError("rand_keys: expected a contiguous CUDA tensor of dtype int32 or uint32")
+    shaped = rewards if rewards is not None else rand_keys
+    if shaped is None:
+        raise TypeError("pods_downsample: rewards or rand_keys is required")
+    B, n = shaped.shape
+    if sel_idx is None:
+        sel_idx = torch.empty((B, max(m, 0)), dtype=torch.int32, device=shaped.device)
+    if sel_k is None:
+        sel_k = torch.empty((B,), dtype=torch.int32, device=shaped.device)
+    _check(load().pods_downsample(_ptr(rewards), _ptr(rand_keys), B, n, m, int(rule), _ptr(sel_idx),
+                                  _ptr(sel_k), _stream(stream)))
+    return sel_idx, sel_k
+
+
+def pods_advantage_before(rewards, sel_idx, std_eps: float = 0.0, adv=None, stream=None):
+    """As pods_advantage, with the mean and standard deviation of all n rewards of each group."""
+    return pods_advantage(rewards, sel_idx, std_eps, adv, stream, _entry="pods_advantage_before")
+
+
+def pods_advantage(rewards, sel_idx, std_eps: float = 0.0, adv=None, stream=None, _entry="pods_advantage"):
     """rewards[B, n] float32, sel_idx[B, m] int32 (device) -> adv[B, m] float32."""
     import torch
     _need(rewards, torch.float32, "rewards")
@@ -122,8 +156,8 @@ def pods_advantage(rewards, sel_idx, std_eps: float = 0.0, adv=None, stream=None
     m = sel_idx.shape[1]
     if adv is None:
         adv = torch.empty((B, m), dtype=torch.float32, device=rewards.device)
-    _check(load().pods_advantage(_ptr(rewards), _ptr(sel_idx), B, n, m, float(std_eps), _ptr(adv),
-                                 _stream(stream)))
+    _check(getattr(load(), _entry)(_ptr(rewards), _ptr(sel_idx), B, n, m, float(std_eps), _ptr(adv),
+                                   _stream(stream)))
     return adv
 
 

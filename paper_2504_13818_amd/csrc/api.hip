@@ -80,19 +80,49 @@ pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m, i
         return fail(PODS_ERR_INVALID_ARG, "pods_select: B=%d n=%d m=%d must be positive", B, n, m);
     if (m > n) return fail(PODS_ERR_INVALID_ARG, "pods_select: m=%d exceeds n=%d", m, n);
     if (n > 4096) return fail(PODS_ERR_UNSUPPORTED, "pods_select: n=%d exceeds 4096", n);
-    return launch_select(rewards, B, n, m, sel_idx, sel_k, static_cast<hipStream_t>(stream));
+    return launch_select(rewards, nullptr, B, n, m, PODS_RULE_MAXVAR, sel_idx, sel_k,
+                         static_cast<hipStream_t>(stream));
+}
+
+pods_status pods_downsample(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n,
+                            int32_t m, pods_rule rule, int32_t* sel_idx, int32_t* sel_k, void* stream) {
+    if (rule != PODS_RULE_MAXVAR && rule != PODS_RULE_MAXR && rule != PODS_RULE_PERC && rule != PODS_RULE_RAND)
+        return fail(PODS_ERR_INVALID_ARG, "pods_downsample: unknown rule %d", (int)rule);
+    if (sel_idx == nullptr) return fail(PODS_ERR_INVALID_ARG, "pods_downsample: sel_idx must not be null");
+    if (rule == PODS_RULE_RAND && rand_keys == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "pods_downsample: the random rule needs rand_keys");
+    if (rule != PODS_RULE_RAND && rewards == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "pods_downsample: rewards must not be null");
+    if (B <= 0 || n <= 0 || m <= 0)
+        return fail(PODS_ERR_INVALID_ARG, "pods_downsample: B=%d n=%d m=%d must be positive", B, n, m);
+    if (m > n) return fail(PODS_ERR_INVALID_ARG, "pods_downsample: m=%d exceeds n=%d", m, n);
+    if (n > 4096) return fail(PODS_ERR_UNSUPPORTED, "pods_downsample: n=%d exceeds 4096", n);
+    return launch_select(rewards, rand_keys, B, n, m, (int32_t)rule, sel_idx, sel_k,
+                         static_cast<hipStream_t>(stream));
+}
+
+static pods_status advantage_entry(const char* who, const float* rewards, const int32_t* sel_idx, int32_t B,
+                                   int32_t n, int32_t m, float std_eps, bool stats_from_all, float* adv,
+                                   void* stream) {
+    if (rewards == nullptr || sel_idx == nullptr || adv == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "%s: null pointer", who);
+    if (B <= 0 || n <= 0 || m <= 0)
+        return fail(PODS_ERR_INVALID_ARG, "%s: B=%d n=%d m=%d must be positive", who, B, n, m);
+    if (m > n) return fail(PODS_ERR_INVALID_ARG, "%s: m=%d exceeds n=%d", who, m, n);
+    if (m > 4096) return fail(PODS_ERR_UNSUPPORTED, "%s: m=%d exceeds 4096", who, m);
+    if (!(std_eps >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "%s: std_eps < 0", who);
+    return launch_advantage(rewards, sel_idx, B, n, m, std_eps, stats_from_all, adv,
+                            static_cast<hipStream_t>(stream));
 }
 
 pods_status pods_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
                            int32_t m, float std_eps, float* adv, void* stream) {
-    if (rewards == nullptr || sel_idx == nullptr || adv == nullptr)
-        return fail(PODS_ERR_INVALID_ARG, "pods_advantage: null pointer");
-    if (B <= 0 || n <= 0 || m <= 0)
-        return fail(PODS_ERR_INVALID_ARG, "pods_advantage: B=%d n=%d m=%d must be positive", B, n, m);
-    if (m > n) return fail(PODS_ERR_INVALID_ARG, "pods_advantage: m=%d exceeds n=%d", m, n);
-    if (m > 4096) return fail(PODS_ERR_UNSUPPORTED, "pods_advantage: m=%d exceeds 4096", m);
-    if (!(std_eps >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "pods_advantage: std_eps < 0");
-    return launch_advantage(rewards, sel_idx, B, n, m, std_eps, adv, static_cast<hipStream_t>(stream));
+    return advantage_entry("pods_advantage", rewards, sel_idx, B, n, m, std_eps, false, adv, stream);
+}
+
+pods_status pods_advantage_before(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
+                                  int32_t m, float std_eps, float* adv, void* stream) {
+    return advantage_entry("pods_advantage_before", rewards, sel_idx, B, n, m, std_eps, true, adv, stream);
 }
 
 static bool loss_sizes_ok(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt) {

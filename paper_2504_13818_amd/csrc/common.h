@@ -52,9 +52,9 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Kernel-family entry points (defined in select.hip, advantage.hip, loss_*.hip).
-pods_status launch_select(const float* rewards, int32_t B, int32_t n, int32_t m, int32_t* sel_idx,
-                          int32_t* sel_k, hipStream_t stream);
+pods_status launch_select(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,
+                          int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream);
 pods_status launch_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
-                             int32_t m, float std_eps, float* adv, hipStream_t stream);
+                             int32_t m, float std_eps, bool stats_from_all, float* adv, hipStream_t stream);
 
 }  // namespace pods

@@ -1,5 +1,6 @@
-// Max-variance down-sampling (Sec. 3.3: Lemma 3.1, Algorithm 2, Theorem 1), one prompt group
-// per wavefront.
+// Down-sampling rules, one prompt group per wavefront: max-variance (Sec. 3.3: Lemma 3.1,
+// Algorithm 2, Theorem 1) and, on the same sorted order, max-reward, percentile and random
+// (Sec. 3.2).
 //
 // Each lane holds KPL consecutive elements of the group as 64-bit sort keys.  A key is the
 // order-preserving integer image of the float32 reward followed by the element's index, laid
@@ -10,9 +11,10 @@
 // lane pattern allows, else through the LDS crossbar (ds_swizzle / ds_bpermute).
 // A bitonic network sorts the 64*KPL keys in registers; the sorted rewards and indices are staged
 // in LDS; prefix sums of r and r^2 over the m lowest and running sums over the k highest are
-// scanned in double precision; one candidate split k per lane is scored as m*Q - S^2 (m^2 times
-// its variance), candidates that repeat the previous multiset are passed over, and a wave
-// arg-max (smallest k on equal scores) picks k.
+// scanned in double precision (DPP row shifts and row broadcasts, no LDS traffic); one candidate
+// split k per lane is scored as m*Q - S^2 (m^2 times its variance), candidates that repeat the
+// previous multiset are passed over, and the wave's maximum plus the first lane that attains it
+// (smallest k on equal scores) picks k.
 #include "common.h"
 
 namespace pods {
@@ -24,6 +26,10 @@ __device__ __forceinline__ double make_key(float r, uint32_t e) {
     r = r + 0.0f;  // -0.0 -> +0.0
     uint32_t b = __float_as_uint(r);
     uint32_t ou = b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);  // unsigned order == float order
+    uint64_t k = (1ull << 62) | ((uint64_t)ou << kIdxBits) | e;
+    return __longlong_as_double((long long)k);
+}
+__device__ __forceinline__ double make_key_u32(uint32_t ou, uint32_t e) {
     uint64_t k = (1ull << 62) | ((uint64_t)ou << kIdxBits) | e;
     return __longlong_as_double((long long)k);
 }
@@ -127,13 +133,45 @@ __device__ __forceinline__ void sort_from(double (&key)[KPL], int lane) {
     }
 }
 
-__device__ __forceinline__ double wave_inclusive_scan(double x, int lane) {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        double t = __shfl_up(x, off, kWave);
-        if (lane >= off) x += t;
-    }
+// x of another lane under a DPP control word; lanes the pattern leaves without a source get `fill`.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double x, double fill) {
+    const int lo = __builtin_amdgcn_update_dpp(__double2loint(fill), __double2loint(x), CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(__double2hiint(fill), __double2hiint(x), CTRL, ROW_MASK, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Inclusive scan over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then lane 15
+// of rows 0 and 2 is broadcast into rows 1 and 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ double wave_inclusive_scan(double x) {
+    x += dpp_f64<0x111, 0xF>(x, 0.0);   // row_shr:1
+    x += dpp_f64<0x112, 0xF>(x, 0.0);   // row_shr:2
+    x += dpp_f64<0x114, 0xF>(x, 0.0);   // row_shr:4
+    x += dpp_f64<0x118, 0xF>(x, 0.0);   // row_shr:8
+    x += dpp_f64<0x142, 0xA>(x, 0.0);   // row_bcast:15 into rows 1, 3
+    x += dpp_f64<0x143, 0xC>(x, 0.0);   // row_bcast:31 into rows 2, 3
     return x;
+}
+
+// Maximum over the 64 lanes, returned wave-uniform (same data movement as the scan; lane 63 ends
+// up with the maximum of everything before it).
+__device__ __forceinline__ double wave_max(double x) {
+    const double ninf = -__builtin_huge_val();
+    x = fmax(x, dpp_f64<0x111, 0xF>(x, ninf));
+    x = fmax(x, dpp_f64<0x112, 0xF>(x, ninf));
+    x = fmax(x, dpp_f64<0x114, 0xF>(x, ninf));
+    x = fmax(x, dpp_f64<0x118, 0xF>(x, ninf));
+    x = fmax(x, dpp_f64<0x142, 0xA>(x, ninf));
+    x = fmax(x, dpp_f64<0x143, 0xC>(x, ninf));
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), kWave - 1);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), kWave - 1);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double lane_value(double x, int src_lane) {   // src_lane wave-uniform
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src_lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src_lane);
+    return __hiloint2double(hi, lo);
 }
 
 // Dynamic LDS per wave: float val[N]; uint16 idx[N]; double p1[m+1]; double p2[m+1].
@@ -145,7 +183,8 @@ __host__ __device__ inline size_t wave_lds_bytes(int N, int m) {
 
 template <int KPL, int WAVES>
 __global__ __launch_bounds__(WAVES* kWave) void select_kernel(const float* __restrict__ rewards,
-                                                              int B, int n, int m,
+                                                              const uint32_t* __restrict__ rand_keys,
+                                                              int B, int n, int m, int rule,
                                                               int32_t* __restrict__ sel_idx,
                                                               int32_t* __restrict__ sel_k) {
     constexpr int N = kWave * KPL;
@@ -163,11 +202,20 @@ __global__ __launch_bounds__(WAVES* kWave) void select_kernel(const float* __res
 
     // ---- load and key (Alg. 2 step 1 input) ----
     double key[KPL];
-    const float* row = rewards + (size_t)(live ? group : 0) * n;
+    if (rule == PODS_RULE_RAND) {   // the m smallest of the caller's random keys, ties by index
+        const uint32_t* row = rand_keys + (size_t)(live ? group : 0) * n;
 #pragma unroll
-    for (int j = 0; j < KPL; ++j) {
-        const int e = lane * KPL + j;
-        key[j] = (e < n) ? make_key(row[e], (uint32_t)e) : pad_key((uint32_t)e);
+        for (int j = 0; j < KPL; ++j) {
+            const int e = lane * KPL + j;
+            key[j] = (e < n) ? make_key_u32(row[e], (uint32_t)e) : pad_key((uint32_t)e);
+        }
+    } else {
+        const float* row = rewards + (size_t)(live ? group : 0) * n;
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+            const int e = lane * KPL + j;
+            key[j] = (e < n) ? make_key(row[e], (uint32_t)e) : pad_key((uint32_t)e);
+        }
     }
 
     // ---- argsort ascending by (reward, index) ----
@@ -181,49 +229,64 @@ __global__ __launch_bounds__(WAVES* kWave) void select_kernel(const float* __res
     }
     __syncthreads();
 
+    if (rule != PODS_RULE_MAXVAR) {
+        // Sec. 3.2's other rules are positions of the sorted order: the m highest (max-reward), the
+        // (j + 1/2)/m quantiles taken as position floor((2j + 1) n / (2m)) (percentile), and the m
+        // lowest of the random keys (random).
+        if (live) {
+            int32_t* out = sel_idx + (size_t)group * m;
+            for (int j = lane; j < m; j += kWave) {
+                int pos = j;
+                if (rule == PODS_RULE_MAXR) pos = n - m + j;
+                if (rule == PODS_RULE_PERC) pos = (int)(((int64_t)(2 * j + 1) * n) / (2 * m));
+                out[j] = (int32_t)s_idx[pos];
+            }
+            if (sel_k != nullptr && lane == 0) sel_k[group] = (rule == PODS_RULE_MAXR) ? m : -1;
+        }
+        return;
+    }
+
     // ---- Theorem 1: prefix sums of r and r^2 over the m lowest ----
     double c1 = 0.0, c2 = 0.0;
     if (lane == 0) { p1[0] = 0.0; p2[0] = 0.0; }
     for (int e0 = 0; e0 < m; e0 += kWave) {
         const int e = e0 + lane;
         const double x = (e < m) ? (double)s_val[e] : 0.0;
-        const double a1 = wave_inclusive_scan(x, lane) + c1;
-        const double a2 = wave_inclusive_scan(x * x, lane) + c2;
+        const double a1 = wave_inclusive_scan(x) + c1;
+        const double a2 = wave_inclusive_scan(x * x) + c2;
         if (e < m) { p1[e + 1] = a1; p2[e + 1] = a2; }
-        c1 = __shfl(a1, kWave - 1, kWave);
-        c2 = __shfl(a2, kWave - 1, kWave);
+        c1 = lane_value(a1, kWave - 1);
+        c2 = lane_value(a2, kWave - 1);
     }
     __syncthreads();
 
     // ---- Alg. 2 steps 2-6: score every split k, keep the first strict maximum ----
-    double best = -__builtin_huge_val();
-    int best_k = 0x7fffffff;
+    // k = 0 (the m lowest) is the starting candidate; lane l of pass k0 scores k = k0 + l + 1.
+    const double dm = (double)m;
+    double best = dm * c2 - c1 * c1;   // wave-uniform
+    int best_k = 0;
     c1 = 0.0;
     c2 = 0.0;
-    const double dm = (double)m;
-    for (int k0 = 0; k0 <= m; k0 += kWave) {
-        const int k = k0 + lane;
-        const bool in = (k >= 1) && (k <= m);
+    for (int k0 = 0; k0 < m; k0 += kWave) {
+        const int k = k0 + lane + 1;
+        const bool in = k <= m;
         const float top = in ? s_val[n - k] : 0.0f;
         const double x = (double)top;
-        const double u1 = wave_inclusive_scan(x, lane) + c1;   // sum of the k highest
-        const double u2 = wave_inclusive_scan(x * x, lane) + c2;
-        c1 = __shfl(u1, kWave - 1, kWave);
-        c2 = __shfl(u2, kWave - 1, kWave);
-        bool eligible = (k == 0);
-        if (in) eligible = (top != s_val[m - k]);   // else same multiset as split k-1
-        if (eligible) {
+        const double u1 = wave_inclusive_scan(x) + c1;   // sum of the k highest
+        const double u2 = wave_inclusive_scan(x * x) + c2;
+        c1 = lane_value(u1, kWave - 1);
+        c2 = lane_value(u2, kWave - 1);
+        double D = -__builtin_huge_val();
+        if (in && top != s_val[m - k]) {   // else same multiset as split k-1
             const double S = p1[m - k] + u1;
             const double Q = p2[m - k] + u2;
-            const double D = dm * Q - S * S;
-            if (D > best) { best = D; best_k = k; }
+            D = dm * Q - S * S;
         }
-    }
-#pragma unroll
-    for (int off = kWave / 2; off >= 1; off >>= 1) {
-        const double ob = __shfl_xor(best, off, kWave);
-        const int ok = __shfl_xor(best_k, off, kWave);
-        if (ob > best || (ob == best && ok < best_k)) { best = ob; best_k = ok; }
+        const double top_d = wave_max(D);
+        if (top_d > best) {   // strictly larger only: an earlier (smaller) k keeps its place on ties
+            best = top_d;
+            best_k = k0 + 1 + (int)__builtin_ctzll(__ballot(D == top_d));
+        }
     }
 
     // ---- emit the (m-k) lowest then the k highest ----
@@ -236,8 +299,8 @@ __global__ __launch_bounds__(WAVES* kWave) void select_kernel(const float* __res
 }
 
 template <int KPL, int WAVES>
-pods_status launch_variant(const float* rewards, int32_t B, int32_t n, int32_t m, int32_t* sel_idx,
-                           int32_t* sel_k, hipStream_t stream) {
+pods_status launch_variant(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,
+                           int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
     const size_t lds = (size_t)WAVES * wave_lds_bytes(kWave * KPL, m);
     if (lds > 160 * 1024) return fail(PODS_ERR_UNSUPPORTED, "pods_select: LDS need %zu B", lds);
     auto kernel = select_kernel<KPL, WAVES>;
@@ -249,22 +312,22 @@ pods_status launch_variant(const float* rewards, int32_t B, int32_t n, int32_t m
                         hipGetErrorString(e));
     }
     const unsigned grid = (unsigned)ceil_div(B, WAVES);
-    PODS_LAUNCH("pods_select", stream, kernel, dim3(grid), dim3(WAVES * kWave), lds, stream, rewards, B, n, m,
-                       sel_idx, sel_k);
+    PODS_LAUNCH("pods_select", stream, kernel, dim3(grid), dim3(WAVES * kWave), lds, stream, rewards, rand_keys,
+                B, n, m, rule, sel_idx, sel_k);
     return check_launch("pods_select");
 }
 
 }  // namespace
 
-pods_status launch_select(const float* rewards, int32_t B, int32_t n, int32_t m, int32_t* sel_idx,
-                          int32_t* sel_k, hipStream_t stream) {
-    if (n <= 64) return launch_variant<1, 4>(rewards, B, n, m, sel_idx, sel_k, stream);
-    if (n <= 128) return launch_variant<2, 4>(rewards, B, n, m, sel_idx, sel_k, stream);
-    if (n <= 256) return launch_variant<4, 4>(rewards, B, n, m, sel_idx, sel_k, stream);
-    if (n <= 512) return launch_variant<8, 2>(rewards, B, n, m, sel_idx, sel_k, stream);
-    if (n <= 1024) return launch_variant<16, 2>(rewards, B, n, m, sel_idx, sel_k, stream);
-    if (n <= 2048) return launch_variant<32, 1>(rewards, B, n, m, sel_idx, sel_k, stream);
-    if (n <= 4096) return launch_variant<64, 1>(rewards, B, n, m, sel_idx, sel_k, stream);
+pods_status launch_select(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,
+                          int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
+    if (n <= 64) return launch_variant<1, 4>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
+    if (n <= 128) return launch_variant<2, 4>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
+    if (n <= 256) return launch_variant<4, 4>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
+    if (n <= 512) return launch_variant<8, 2>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
+    if (n <= 1024) return launch_variant<16, 2>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
+    if (n <= 2048) return launch_variant<32, 1>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
+    if (n <= 4096) return launch_variant<64, 1>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
     return fail(PODS_ERR_UNSUPPORTED, "pods_select: n = %d exceeds 4096", n);
 }
 
