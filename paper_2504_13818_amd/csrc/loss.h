@@ -46,7 +46,7 @@ __device__ __forceinline__ float g_range_scale(const LossHeader* hdr) {
 }
 
 // Fixed power-of-two scales of the fp16 operands of the two gradient contractions.
-constexpr float kQScale = 16384.0f;  // q = kQScale (1[v=y] - softmax): |q| <= 2^14
+constexpr float kQScale = 16384.0f;  // q = kQScale softmax (0 at v = y): 0 <= q <= 2^14
 constexpr float kWScale = 256.0f;    // fp16 weight copies hold kWScale * W
 constexpr float kHScale = 0.0625f;   // fp16 transposed hidden copy holds kHScale * h
 

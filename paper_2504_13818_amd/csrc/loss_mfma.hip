@@ -5,7 +5,7 @@
 // v_mfma_f32_32x32x16_bf16 and fp32 accumulators:
 //
 //   forward    z[v][t]  = sum_k W[v][k]   H[t][k]       -> running (max, sum exp) per token, z_y
-//   recompute  z[v][t]  (same)                          -> q = -2^14 exp(z - lse) as fp16 (0 at v = y)
+//   recompute  z[v][t]  (same)                          -> q = 2^14 exp(z - lse) as fp16 (0 at v = y)
 //   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times g_t, accumulated over vocab chunks
 //   d_w_lm     dW[k][v] = sum_t H16[t][k] q[t][v]       -> complete per vocabulary chunk
 //
@@ -13,7 +13,7 @@
 // in d_w_lm) is staged in LDS as it lies in memory and read with the transposing LDS load, so q is
 // stored once (token-major) and no transposed copy of any matrix exists.
 //
-// The per-logit gradient is dz = g_t q / 2^14 for v != y.  q is kept in fp16 (11-bit significand)
+// The per-logit gradient is dz = -g_t q / 2^14 for v != y.  q is kept in fp16 (11-bit significand)
 // rather than bf16 (8-bit) so that a logit with a large probability does not carry a 2^-8 error
 // into its token's gradient.  The token weight g_t, which spans many binades, never enters q:
 // d_hidden applies it per output row, and d_w_lm folds it into H16 = fp16(g_t h_t 2^-e) with one
@@ -442,7 +442,7 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 
 // ------------------------------------------------------------------------------------------
 // Backward step 1 (per vocabulary chunk): recompute the logits tile and form
-// q = -kQScale exp(z - lse), rounded to fp16, 0 at v = y, token-major (dz = g q / kQScale).
+// q = kQScale exp(z - lse), rounded to fp16, 0 at v = y, token-major (dz = -g q / kQScale).
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void recompute_kernel(
     const LossHeader* __restrict__ hdr, const int32_t* __restrict__ tok,
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                val[mi][r] = -__builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e * kInvLogitScale, off));
+                val[mi][r] = __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e * kInvLogitScale, off));
         const int slot = acc_slot_of(y - vbase);
         if (__any(slot >= 0)) {
 #pragma unroll
@@ -512,7 +512,7 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward step 2: d_hidden[t][k] += (g_t / (kQScale kWScale)) sum_{v in chunk} q[t][v] W16[v][k]
+// Backward step 2: d_hidden[t][k] -= (g_t / (kQScale kWScale)) sum_{v in chunk} q[t][v] W16[v][k]
 // (the rows were initialised with the y-logit term)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict__ hdr,
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     for (int ni = 0; ni < 4; ++ni) {
         const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
         if (p >= n_valid) continue;
-        const float scale = gvec[p] * (1.0f / (kQScale * kWScale));
+        const float scale = gvec[p] * (-1.0f / (kQScale * kWScale));
         float* row = d_hidden + (int64_t)row_map[p] * d;
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
@@ -559,7 +559,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward step 3: d_w_lm[v][k] = (1 / (kQScale s)) sum_t q[t][v] H16[t][k], H16 = g_t h_t s
+// Backward step 3: d_w_lm[v][k] = -(1 / (kQScale s)) sum_t q[t][v] H16[t][k], H16 = g_t h_t s
 // (all tokens: complete per chunk)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict__ hdr,
@@ -582,7 +582,7 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
     zero_acc(acc);
     const int KT = (n_valid + kBK - 1) / kBK;
     if (KT > 0) k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
-    const float scale = 1.0f / (kQScale * g_range_scale(hdr));
+    const float scale = -1.0f / (kQScale * g_range_scale(hdr));
 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
