@@ -29,11 +29,16 @@ PROBE_BYTES = 1 << 30         # the calibration copy reads and writes this many 
 
 
 LOSS_SOURCES = ("common.h", "loss.h", "loss.hip", "loss_mfma.hip")
+SELECT_SOURCES = ("common.h", "select.hip")
+
+
+def sources_of(kernel):
+    return SELECT_SOURCES if kernel == "pods_select" else LOSS_SOURCES
 
 
 def source_digest(names=LOSS_SOURCES):
-    """sha256 over the token-loss HIP sources: HBM-traffic counters are only quoted for the kernels
-    they were taken on."""
+    """sha256 over a kernel family's HIP sources: HBM-traffic counters are only quoted for the
+    kernels they were taken on."""
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2504_13818_amd", "csrc")
@@ -68,7 +73,7 @@ def summarize_traffic(fetch_csv, write_csv, out_path=TRAFFIC_FILE):
 
     fetch, f_fac, f_probe = load(fetch_csv, "FETCH_SIZE")
     write, w_fac, w_probe = load(write_csv, "WRITE_SIZE")
-    out = {"source_sha256": source_digest(),
+    out = {"source_sha256": {"loss": source_digest(LOSS_SOURCES), "select": source_digest(SELECT_SOURCES)},
            "calibration": {"probe": "torch.mul(x, 1.0, out=y) on 2^28 fp32 elements: reads 1 GiB, writes 1 GiB",
                            "fetch_factor": f_fac, "fetch_probe_kib": f_probe,
                            "write_factor": w_fac, "write_probe_kib": w_probe},
@@ -85,7 +90,8 @@ def recorded_traffic(kernel):
         t = json.load(open(TRAFFIC_FILE))
     except (OSError, ValueError):
         return None
-    if t.get("source_sha256") != source_digest():
+    family = "select" if kernel == "pods_select" else "loss"
+    if (t.get("source_sha256") or {}).get(family) != source_digest(sources_of(kernel)):
         return None
     k = t.get("kernels", {}).get(kernel)
     if not k or k.get("fetch_bytes_per_launch") is None or k.get("write_bytes_per_launch") is None:
@@ -132,8 +138,8 @@ def time_selector(lib, torch, inputs, steps):
     return dict(workload="selector-stress B=65536 n=256 m=64 fp32", ms_per_launch=ms,
                 groups_per_s=B / (ms * 1e-3), launches=len(prof),
                 roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s",
-                              frac=gbs / PEAK_HBM_GBS, traffic=None,   # not taken for this kernel yet
-                              bytes_per_group=bytes_per_group))
+                              frac=gbs / PEAK_HBM_GBS, traffic=recorded_traffic("pods_select"),
+                              bytes_per_launch=bytes_per_group * B, bytes_per_group=bytes_per_group))
 
 
 def cpu_selector(inputs):
@@ -147,7 +153,7 @@ def cpu_selector(inputs):
                 sample="all 65536 groups of the selector-stress workload, C oracle, OpenMP")
 
 
-def cpu_loss(inputs, cfg, tokens_sample=1024):
+def cpu_loss(inputs, cfg, tokens_sample=4096):
     """The numpy oracle (fp32 GEMM, fp64 reductions) forward + backward on a bounded sample."""
     import numpy as np
     from oracle import pods_oracle as po
@@ -173,8 +179,8 @@ def cpu_loss(inputs, cfg, tokens_sample=1024):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, choices=[1, 2, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -242,14 +248,18 @@ def main():
         torch.cuda.synchronize()
         del px, py
     lib.pods_profile_enable(True)               # HIP events around every launch, on the launch stream
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # same stream as the launches
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     prof = lib.pods_profile_read()
     lib.pods_profile_enable(False)
     ms_per_step = wall * 1e3 / args.steps
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     loss_val = float(out["loss"].cpu()[0])
     assert np.isfinite(loss_val)
 
@@ -281,7 +291,8 @@ def main():
     result = {
         "metric": "GRPO token-loss fwd+bwd tokens/s (% MFMA peak); pods_select groups/s (% HBM)",
         "value": n_valid / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_median": step_ms[len(step_ms) // 2],
+        "ms_per_step_min": step_ms[0], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": c["dtype"], "data": "synthetic",
         "config": {"workload": f"configs[{cfg}] {c['name']}: B={B} n={n} m={m} R={R} T={T} "
                                f"valid_tokens={n_valid} d={d} V={V} {c['dtype']} eps={c['clip_eps']}",
