@@ -91,7 +91,8 @@ def recorded_traffic(kernel):
     except (OSError, ValueError):
         return None
     family = "select" if kernel == "pods_select" else "loss"
-    if (t.get("source_sha256") or {}).get(family) != source_digest(sources_of(kernel)):
+    digests = t.get("source_sha256")
+    if not isinstance(digests, dict) or digests.get(family) != source_digest(sources_of(kernel)):
         return None
     k = t.get("kernels", {}).get(kernel)
     if not k or k.get("fetch_bytes_per_launch") is None or k.get("write_bytes_per_launch") is None:

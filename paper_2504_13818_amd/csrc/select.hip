@@ -1,20 +1,27 @@
-// Down-sampling rules, one prompt group per wavefront: max-variance (Sec. 3.3: Lemma 3.1,
-// Algorithm 2, Theorem 1) and, on the same sorted order, max-reward, percentile and random
-// (Sec. 3.2).
+// Down-sampling rules: max-variance (Sec. 3.3: Lemma 3.1, Algorithm 2, Theorem 1) and, on the
+// same sorted order, max-reward, percentile and random (Sec. 3.2).
 //
-// Each lane holds KPL consecutive elements of the group as 64-bit sort keys.  A key is the
-// order-preserving integer image of the float32 reward followed by the element's index, laid
-// into the mantissa of a double in [2, 4): for such doubles floating-point order equals integer
-// order, so an in-lane compare-exchange is one v_min_f64 and one v_max_f64 and a cross-lane one is
-// one v_cmp_lt_f64 and two selects.  The index in the low bits makes every key distinct and gives
-// the (reward, index) order the tie rule asks for.  Partner values travel by DPP moves where the
-// lane pattern allows, else through the LDS crossbar (ds_swizzle / ds_bpermute).
-// A bitonic network sorts the 64*KPL keys in registers; the sorted rewards and indices are staged
-// in LDS; prefix sums of r and r^2 over the m lowest and running sums over the k highest are
-// scanned in double precision (DPP row shifts and row broadcasts, no LDS traffic); one candidate
-// split k per lane is scored as m*Q - S^2 (m^2 times its variance), candidates that repeat the
-// previous multiset are passed over, and the wave's maximum plus the first lane that attains it
-// (smallest k on equal scores) picks k.
+// A prompt group is sorted by G lanes of a wavefront, KPL keys per lane (G * KPL >= n), so one
+// wavefront handles 64 / G groups at once.  Few lanes per group is the point: a compare-exchange
+// between two keys of the same lane is one v_min_f64 plus one v_max_f64, one between lanes costs
+// two data moves, a minimum and a sign flip per key, so for n = 256 eight lanes with 32 keys each
+// run 30 of the 36 bitonic stages inside the lane.  (Between lanes the compare is avoided too: see
+// set_sign.)
+//
+// A key is the order-preserving integer image of the float32 reward followed by the element's
+// index, laid into the mantissa of a double in [2, 4): for such doubles floating-point order equals
+// integer order.  The index in the low bits makes every key distinct and gives the (reward, index)
+// order the tie rule asks for.  Partner values travel by DPP moves (every lane pattern inside a
+// row of 16 lanes has one), through the LDS crossbar (ds_swizzle) up to 32 lanes, by ds_bpermute
+// beyond.
+//
+// After the sort the m lowest and the m highest (reward, index) pairs of each group are staged in
+// LDS.  Each lane of the group then owns a contiguous block of the candidate splits k: it sums its
+// block of the lowest / highest rewards and their squares in double precision, a scan over the G
+// lanes turns block sums into block offsets, and the lane walks its candidates in ascending k,
+// scoring m*Q - S^2 (m^2 times the variance) from the prefix sums of Theorem 1.  Candidates that
+// repeat the previous multiset are passed over; a strictly larger score replaces the running best,
+// and across lanes the larger score, or on equal scores the smaller k, wins.
 #include "common.h"
 
 namespace pods {
@@ -22,21 +29,16 @@ namespace {
 
 constexpr int kIdxBits = 12;  // n <= 4096
 
-__device__ __forceinline__ double make_key(float r, uint32_t e) {
-    r = r + 0.0f;  // -0.0 -> +0.0
-    uint32_t b = __float_as_uint(r);
-    uint32_t ou = b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);  // unsigned order == float order
-    uint64_t k = (1ull << 62) | ((uint64_t)ou << kIdxBits) | e;
-    return __longlong_as_double((long long)k);
-}
 __device__ __forceinline__ double make_key_u32(uint32_t ou, uint32_t e) {
     uint64_t k = (1ull << 62) | ((uint64_t)ou << kIdxBits) | e;
     return __longlong_as_double((long long)k);
 }
-__device__ __forceinline__ double pad_key(uint32_t e) {
-    uint64_t k = (1ull << 62) | ((uint64_t)0xFFFFFFFFu << kIdxBits) | e;  // after every real reward
-    return __longlong_as_double((long long)k);
+__device__ __forceinline__ double make_key(float r, uint32_t e) {
+    r = r + 0.0f;  // -0.0 -> +0.0
+    uint32_t b = __float_as_uint(r);
+    return make_key_u32(b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u), e);  // unsigned order == float order
 }
+__device__ __forceinline__ double pad_key(uint32_t e) { return make_key_u32(0xFFFFFFFFu, e); }  // after every real key
 __device__ __forceinline__ float key_reward(double key) {
     uint64_t k = (uint64_t)__double_as_longlong(key);
     uint32_t ou = (uint32_t)(k >> kIdxBits);
@@ -53,10 +55,9 @@ __device__ __forceinline__ void cmp_exchange(double& lo, double& hi) {
     hi = b;
 }
 
-// Value of `x` held by lane (lane ^ LM).  Masks that a DPP modifier can express (1, 2, 3 within a
-// quad, 7 and 15 as half-row / row mirrors) cost one VALU move; other masks below 32 go through the
-// LDS crossbar without touching LDS memory (ds_swizzle, bit mode); masks that cross the two
-// 32-lane halves use ds_bpermute with the partner's lane index.
+// Value of `x` held by lane (lane ^ LM).  Inside a row of 16 lanes every mask the network uses has
+// a DPP form: quad permutes (1, 2, 3), half-row and row mirrors (7, 15), a row rotation (8), and for
+// 4 a shift up plus a shift down, each written to the banks of lanes it is right for.
 template <int LM>
 __device__ __forceinline__ uint32_t lane_xor(uint32_t x, int lane) {
     if constexpr (LM == 1) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);
@@ -64,6 +65,11 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t x, int lane) {
     else if constexpr (LM == 3) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x1B, 0xF, 0xF, true);
     else if constexpr (LM == 7) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x141, 0xF, 0xF, true);
     else if constexpr (LM == 15) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x140, 0xF, 0xF, true);
+    else if constexpr (LM == 8) return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x128, 0xF, 0xF, true);  // row_ror:8
+    else if constexpr (LM == 4) {
+        const int up = __builtin_amdgcn_update_dpp((int)x, (int)x, 0x104, 0xF, 0x5, false);   // row_shl:4 -> lanes 0-3, 8-11
+        return (uint32_t)__builtin_amdgcn_update_dpp(up, (int)x, 0x114, 0xF, 0xA, false);    // row_shr:4 -> lanes 4-7, 12-15
+    }
     else if constexpr (LM < 32) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)x, 0x1F | (LM << 10));
     else return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ LM) << 2, (int)x);
 }
@@ -74,14 +80,23 @@ __device__ __forceinline__ double lane_xor(double x, int lane) {
     return __hiloint2double((int)hi, (int)lo);
 }
 
-// Keys are pairwise distinct, so "mine < other" decides; the lower lane of a pair keeps the smaller.
-__device__ __forceinline__ double keep(double mine, double other, bool lower) {
-    return ((mine < other) == lower) ? mine : other;
+// Compare-exchange between lanes without a compare: for the duration of a cross-lane stage the
+// lane that is to keep the larger key of its pair holds its keys negated (sign bit flipped, which
+// reverses the order of these never-zero doubles).  Then both lanes of a pair compute
+// min(mine, -other): the lower lane gets min(a, b), the upper one min(-b, -a) = -max(a, b).
+// `sign` is the flip this lane's keys currently carry; moving to another stage costs one XOR per key.
+template <int KPL>
+__device__ __forceinline__ void set_sign(double (&key)[KPL], uint32_t& sign, uint32_t want) {
+    const uint32_t delta = sign ^ want;
+#pragma unroll
+    for (int j = 0; j < KPL; ++j)
+        key[j] = __hiloint2double((int)((uint32_t)__double2hiint(key[j]) ^ delta), __double2loint(key[j]));
+    sign = want;
 }
 
 // First step of a bitonic merge of blocks of `SIZE`: element e meets e ^ (SIZE-1).
 template <int KPL, int SIZE>
-__device__ __forceinline__ void stage_mirror(double (&key)[KPL], int lane) {
+__device__ __forceinline__ void stage_mirror(double (&key)[KPL], uint32_t& sign, int lane) {
     if constexpr (SIZE <= KPL) {
 #pragma unroll
         for (int j = 0; j < KPL; ++j) {
@@ -90,19 +105,23 @@ __device__ __forceinline__ void stage_mirror(double (&key)[KPL], int lane) {
         }
     } else {
         constexpr int LM = SIZE / KPL - 1;          // lane ^ LM, register KPL-1-j
-        const bool lower = (lane & ((LM + 1) >> 1)) == 0;
-        double other[KPL];
+        set_sign<KPL>(key, sign, (lane & ((LM + 1) >> 1)) ? 0x80000000u : 0u);
 #pragma unroll
-        for (int j = 0; j < KPL; ++j) other[j] = lane_xor<LM>(key[KPL - 1 - j], lane);
-#pragma unroll
-        for (int j = 0; j < KPL; ++j) key[j] = keep(key[j], other[j], lower);
+        for (int j = 0; j < KPL / 2; ++j) {
+            const double oa = lane_xor<LM>(key[KPL - 1 - j], lane);
+            const double ob = lane_xor<LM>(key[j], lane);
+            key[j] = fmin(key[j], -oa);
+            key[KPL - 1 - j] = fmin(key[KPL - 1 - j], -ob);
+        }
     }
 }
 
 // Later steps of a merge: element e meets e ^ STRIDE.
-template <int KPL, int STRIDE>
-__device__ __forceinline__ void stage_xor(double (&key)[KPL], int lane) {
+template <int KPL, int STRIDE, bool CROSSED>
+__device__ __forceinline__ void stage_xor(double (&key)[KPL], uint32_t& sign, int lane) {
     if constexpr (STRIDE < KPL) {
+        // first in-lane step after cross-lane ones: back to true keys
+        if constexpr (CROSSED && STRIDE == KPL / 2) set_sign<KPL>(key, sign, 0u);
 #pragma unroll
         for (int j = 0; j < KPL; ++j) {
             const int p = j ^ STRIDE;
@@ -110,200 +129,258 @@ __device__ __forceinline__ void stage_xor(double (&key)[KPL], int lane) {
         }
     } else {
         constexpr int LM = STRIDE / KPL;
-        const bool lower = (lane & LM) == 0;
+        set_sign<KPL>(key, sign, (lane & LM) ? 0x80000000u : 0u);
 #pragma unroll
-        for (int j = 0; j < KPL; ++j) key[j] = keep(key[j], lane_xor<LM>(key[j], lane), lower);
+        for (int j = 0; j < KPL; ++j) key[j] = fmin(key[j], -lane_xor<LM>(key[j], lane));
     }
 }
 
-template <int KPL, int SIZE, int STRIDE>
-__device__ __forceinline__ void merge_steps(double (&key)[KPL], int lane) {
+template <int KPL, int STRIDE, bool CROSSED>
+__device__ __forceinline__ void merge_steps(double (&key)[KPL], uint32_t& sign, int lane) {
     if constexpr (STRIDE >= 1) {
-        stage_xor<KPL, STRIDE>(key, lane);
-        merge_steps<KPL, SIZE, STRIDE / 2>(key, lane);
+        stage_xor<KPL, STRIDE, CROSSED>(key, sign, lane);
+        merge_steps<KPL, STRIDE / 2, CROSSED>(key, sign, lane);
     }
 }
 
-template <int KPL, int SIZE>
-__device__ __forceinline__ void sort_from(double (&key)[KPL], int lane) {
-    if constexpr (SIZE <= kWave * KPL) {
-        stage_mirror<KPL, SIZE>(key, lane);
-        merge_steps<KPL, SIZE, SIZE / 4>(key, lane);
-        sort_from<KPL, SIZE * 2>(key, lane);
+// Bitonic sort of the G*KPL keys held by each aligned run of G lanes (element e = lane-in-run * KPL + j).
+template <int KPL, int G, int SIZE>
+__device__ __forceinline__ void sort_from(double (&key)[KPL], uint32_t& sign, int lane) {
+    static_assert(KPL >= 2, "the sign is restored by the first in-lane step of each merge");
+    if constexpr (SIZE <= G * KPL) {
+        stage_mirror<KPL, SIZE>(key, sign, lane);
+        merge_steps<KPL, SIZE / 4, (SIZE > KPL)>(key, sign, lane);
+        sort_from<KPL, G, SIZE * 2>(key, sign, lane);
     }
 }
 
-// x of another lane under a DPP control word; lanes the pattern leaves without a source get `fill`.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ double dpp_f64(double x, double fill) {
-    const int lo = __builtin_amdgcn_update_dpp(__double2loint(fill), __double2loint(x), CTRL, ROW_MASK, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(__double2hiint(fill), __double2hiint(x), CTRL, ROW_MASK, 0xF, false);
-    return __hiloint2double(hi, lo);
+// x of lane (lane - OFF), OFF < 16, 0.0 where that lane lies before the start of the row of 16 lanes
+// or, for runs shorter than a row, before the start of the run.
+template <int G, int OFF>
+__device__ __forceinline__ double run_shift_up(double x, int gl) {
+    static_assert(OFF < 16 && OFF < G, "shift inside a row and inside the run");
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x110 + OFF, 0xF, 0xF, true);   // row_shr:OFF
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x110 + OFF, 0xF, 0xF, true);
+    if constexpr (G >= 16) return __hiloint2double(hi, lo);
+    const bool has = gl >= OFF;
+    return __hiloint2double(has ? hi : 0, has ? lo : 0);
 }
 
-// Inclusive scan over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then lane 15
-// of rows 0 and 2 is broadcast into rows 1 and 3, then lane 31 into rows 2 and 3.
-__device__ __forceinline__ double wave_inclusive_scan(double x) {
-    x += dpp_f64<0x111, 0xF>(x, 0.0);   // row_shr:1
-    x += dpp_f64<0x112, 0xF>(x, 0.0);   // row_shr:2
-    x += dpp_f64<0x114, 0xF>(x, 0.0);   // row_shr:4
-    x += dpp_f64<0x118, 0xF>(x, 0.0);   // row_shr:8
-    x += dpp_f64<0x142, 0xA>(x, 0.0);   // row_bcast:15 into rows 1, 3
-    x += dpp_f64<0x143, 0xC>(x, 0.0);   // row_bcast:31 into rows 2, 3
-    return x;
+// Exclusive prefix sum of x over the lanes of each run of G lanes (lane 0 of the run gets 0).
+template <int G>
+__device__ __forceinline__ double run_exclusive_scan(double x, int gl, int lane) {
+    if constexpr (G >= 2) x += run_shift_up<G, 1>(x, gl);
+    if constexpr (G >= 4) x += run_shift_up<G, 2>(x, gl);
+    if constexpr (G >= 8) x += run_shift_up<G, 4>(x, gl);
+    if constexpr (G >= 16) x += run_shift_up<G, 8>(x, gl);
+    if constexpr (G >= 32) {           // lane 15 of rows 0 and 2 into rows 1 and 3
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x142, 0xA, 0xF, false);
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x142, 0xA, 0xF, false);
+        x += __hiloint2double(hi, lo);
+    }
+    if constexpr (G >= 64) {           // lane 31 into rows 2 and 3
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x143, 0xC, 0xF, false);
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x143, 0xC, 0xF, false);
+        x += __hiloint2double(hi, lo);
+    }
+    // inclusive -> exclusive: the left neighbour's value
+    const int lo = __builtin_amdgcn_ds_bpermute(((lane - 1) & (kWave - 1)) << 2, __double2loint(x));
+    const int hi = __builtin_amdgcn_ds_bpermute(((lane - 1) & (kWave - 1)) << 2, __double2hiint(x));
+    return gl == 0 ? 0.0 : __hiloint2double(hi, lo);
 }
 
-// Maximum over the 64 lanes, returned wave-uniform (same data movement as the scan; lane 63 ends
-// up with the maximum of everything before it).
-__device__ __forceinline__ double wave_max(double x) {
-    const double ninf = -__builtin_huge_val();
-    x = fmax(x, dpp_f64<0x111, 0xF>(x, ninf));
-    x = fmax(x, dpp_f64<0x112, 0xF>(x, ninf));
-    x = fmax(x, dpp_f64<0x114, 0xF>(x, ninf));
-    x = fmax(x, dpp_f64<0x118, 0xF>(x, ninf));
-    x = fmax(x, dpp_f64<0x142, 0xA>(x, ninf));
-    x = fmax(x, dpp_f64<0x143, 0xC>(x, ninf));
-    const int lo = __builtin_amdgcn_readlane(__double2loint(x), kWave - 1);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), kWave - 1);
-    return __hiloint2double(hi, lo);
+// Best (score, k) over the lanes of a run: the larger score, on equal scores the smaller k.
+template <int LM>
+__device__ __forceinline__ void run_best(double& best, int& best_k, int lane) {
+    if constexpr (LM >= 1) {
+        const double ob = lane_xor<LM>(best, lane);
+        const int ok = (int)lane_xor<LM>((uint32_t)best_k, lane);
+        if (ob > best || (ob == best && ok < best_k)) { best = ob; best_k = ok; }
+        run_best<LM / 2>(best, best_k, lane);
+    }
 }
 
-__device__ __forceinline__ double lane_value(double x, int src_lane) {   // src_lane wave-uniform
-    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src_lane);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src_lane);
-    return __hiloint2double(hi, lo);
+// Sorted positions [first, first + count) to LDS; this lane holds positions e0 .. e0 + KPL - 1, which
+// usually lie wholly inside or wholly outside the range.
+template <int KPL>
+__device__ __forceinline__ void stage_range(const double (&key)[KPL], int e0, int first, int count,
+                                            float* vals, uint16_t* idxs) {
+    if (e0 >= first && e0 + KPL <= first + count) {
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+            vals[e0 - first + j] = key_reward(key[j]);
+            idxs[e0 - first + j] = (uint16_t)key_index(key[j]);
+        }
+    } else if (e0 + KPL > first && e0 < first + count) {
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+            const int p = e0 + j;
+            if (p >= first && p < first + count) {
+                vals[p - first] = key_reward(key[j]);
+                idxs[p - first] = (uint16_t)key_index(key[j]);
+            }
+        }
+    }
 }
 
-// Dynamic LDS per wave: float val[N]; uint16 idx[N]; double p1[m+1]; double p2[m+1].
-__host__ __device__ inline size_t wave_lds_bytes(int N, int m) {
-    size_t b = (size_t)N * 4 + (size_t)N * 2;
-    b = (b + 7) / 8 * 8;
-    return b + 2 * (size_t)(m + 1) * 8;
+// LDS per group.  Max-variance: float lo[m], hi[m]; uint16 ilo[m], ihi[m]; double p1[m+1], p2[m+1].
+// Other rules: uint16 idx[n].
+__host__ __device__ inline size_t group_lds_bytes(int n, int m, int rule) {
+    if (rule != PODS_RULE_MAXVAR) return ((size_t)n * 2 + 15) / 16 * 16;
+    return ((size_t)m * 12 + 15) / 16 * 16 + 2 * (size_t)(m + 1) * 8;
 }
 
-template <int KPL, int WAVES>
-__global__ __launch_bounds__(WAVES* kWave) void select_kernel(const float* __restrict__ rewards,
-                                                              const uint32_t* __restrict__ rand_keys,
-                                                              int B, int n, int m, int rule,
-                                                              int32_t* __restrict__ sel_idx,
-                                                              int32_t* __restrict__ sel_k) {
-    constexpr int N = kWave * KPL;
+template <int KPL, int G>
+__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ rewards,
+                                                     const uint32_t* __restrict__ rand_keys,
+                                                     int B, int n, int m, int rule,
+                                                     int32_t* __restrict__ sel_idx,
+                                                     int32_t* __restrict__ sel_k) {
+    constexpr int kGroupsPerWave = kWave / G;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int group = blockIdx.x * WAVES + wave;
-    const bool live = group < B;  // dead waves still take every barrier
+    const int waves = blockDim.x / kWave;
+    const int gl = lane & (G - 1);                 // lane within the group's run
+    const int slot = wave * kGroupsPerWave + lane / G;
+    const int64_t group = (int64_t)blockIdx.x * (waves * kGroupsPerWave) + slot;
+    const bool live = group < B;                   // dead runs still take every barrier
 
-    unsigned char* base = lds_raw + (size_t)wave * wave_lds_bytes(N, m);
-    float* s_val = reinterpret_cast<float*>(base);
-    uint16_t* s_idx = reinterpret_cast<uint16_t*>(base + (size_t)N * 4);
-    double* p1 = reinterpret_cast<double*>(base + ((size_t)N * 6 + 7) / 8 * 8);
-    double* p2 = p1 + (m + 1);
-
-    // ---- load and key (Alg. 2 step 1 input) ----
+    // ---- load and key (Alg. 2 step 1 input): lane gl holds elements gl*KPL .. gl*KPL + KPL-1 ----
     double key[KPL];
+    const int e0 = gl * KPL;
     if (rule == PODS_RULE_RAND) {   // the m smallest of the caller's random keys, ties by index
         const uint32_t* row = rand_keys + (size_t)(live ? group : 0) * n;
 #pragma unroll
-        for (int j = 0; j < KPL; ++j) {
-            const int e = lane * KPL + j;
-            key[j] = (e < n) ? make_key_u32(row[e], (uint32_t)e) : pad_key((uint32_t)e);
-        }
+        for (int j = 0; j < KPL; ++j)
+            key[j] = (e0 + j < n) ? make_key_u32(row[e0 + j], (uint32_t)(e0 + j)) : pad_key((uint32_t)(e0 + j));
     } else {
         const float* row = rewards + (size_t)(live ? group : 0) * n;
+        if (KPL >= 4 && n == G * KPL && (reinterpret_cast<uintptr_t>(rewards) & 15) == 0) {
+            // full rows of 16-byte-aligned lane blocks
 #pragma unroll
-        for (int j = 0; j < KPL; ++j) {
-            const int e = lane * KPL + j;
-            key[j] = (e < n) ? make_key(row[e], (uint32_t)e) : pad_key((uint32_t)e);
+            for (int j = 0; j + 3 < KPL; j += 4) {
+                const float4 v = *reinterpret_cast<const float4*>(row + e0 + j);
+                key[j] = make_key(v.x, (uint32_t)(e0 + j));
+                key[j + 1] = make_key(v.y, (uint32_t)(e0 + j + 1));
+                key[j + 2] = make_key(v.z, (uint32_t)(e0 + j + 2));
+                key[j + 3] = make_key(v.w, (uint32_t)(e0 + j + 3));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < KPL; ++j)
+                key[j] = (e0 + j < n) ? make_key(row[e0 + j], (uint32_t)(e0 + j)) : pad_key((uint32_t)(e0 + j));
         }
     }
 
-    // ---- argsort ascending by (reward, index) ----
-    sort_from<KPL, 2>(key, lane);
+    // ---- argsort ascending by (key, index): sorted position p = gl*KPL + j ----
+    uint32_t sign = 0u;
+    sort_from<KPL, G, 2>(key, sign, lane);
 
-#pragma unroll
-    for (int j = 0; j < KPL; ++j) {
-        const int e = lane * KPL + j;
-        s_val[e] = key_reward(key[j]);
-        s_idx[e] = (uint16_t)key_index(key[j]);
-    }
-    __syncthreads();
-
+    unsigned char* base = lds_raw + (size_t)slot * group_lds_bytes(n, m, rule);
     if (rule != PODS_RULE_MAXVAR) {
         // Sec. 3.2's other rules are positions of the sorted order: the m highest (max-reward), the
         // (j + 1/2)/m quantiles taken as position floor((2j + 1) n / (2m)) (percentile), and the m
         // lowest of the random keys (random).
+        uint16_t* s_idx = reinterpret_cast<uint16_t*>(base);
+#pragma unroll
+        for (int j = 0; j < KPL; ++j)
+            if (e0 + j < n) s_idx[e0 + j] = (uint16_t)key_index(key[j]);
+        __syncthreads();
         if (live) {
             int32_t* out = sel_idx + (size_t)group * m;
-            for (int j = lane; j < m; j += kWave) {
+            for (int j = gl; j < m; j += G) {
                 int pos = j;
                 if (rule == PODS_RULE_MAXR) pos = n - m + j;
                 if (rule == PODS_RULE_PERC) pos = (int)(((int64_t)(2 * j + 1) * n) / (2 * m));
                 out[j] = (int32_t)s_idx[pos];
             }
-            if (sel_k != nullptr && lane == 0) sel_k[group] = (rule == PODS_RULE_MAXR) ? m : -1;
+            if (sel_k != nullptr && gl == 0) sel_k[group] = (rule == PODS_RULE_MAXR) ? m : -1;
         }
         return;
     }
 
-    // ---- Theorem 1: prefix sums of r and r^2 over the m lowest ----
-    double c1 = 0.0, c2 = 0.0;
-    if (lane == 0) { p1[0] = 0.0; p2[0] = 0.0; }
-    for (int e0 = 0; e0 < m; e0 += kWave) {
-        const int e = e0 + lane;
-        const double x = (e < m) ? (double)s_val[e] : 0.0;
-        const double a1 = wave_inclusive_scan(x) + c1;
-        const double a2 = wave_inclusive_scan(x * x) + c2;
-        if (e < m) { p1[e + 1] = a1; p2[e + 1] = a2; }
-        c1 = lane_value(a1, kWave - 1);
-        c2 = lane_value(a2, kWave - 1);
+    float* s_lo = reinterpret_cast<float*>(base);                 // rewards at positions 0 .. m-1
+    float* s_hi = s_lo + m;                                       // rewards at positions n-m .. n-1
+    uint16_t* i_lo = reinterpret_cast<uint16_t*>(s_hi + m);
+    uint16_t* i_hi = i_lo + m;
+    double* p1 = reinterpret_cast<double*>(base + ((size_t)m * 12 + 15) / 16 * 16);
+    double* p2 = p1 + (m + 1);
+    stage_range<KPL>(key, e0, 0, m, s_lo, i_lo);
+    stage_range<KPL>(key, e0, n - m, m, s_hi, i_hi);
+    __syncthreads();
+
+    // ---- Theorem 1: prefix sums of r and r^2 over the m lowest; lane gl owns positions [j0, j1) ----
+    const int per_lane = (m + G - 1) / G;
+    const int j0 = min(m, gl * per_lane), j1 = min(m, j0 + per_lane);
+    double b1 = 0.0, b2 = 0.0;
+    for (int j = j0; j < j1; ++j) {
+        const double x = (double)s_lo[j];
+        b1 += x;
+        b2 += x * x;
     }
+    double r1 = run_exclusive_scan<G>(b1, gl, lane);
+    double r2 = run_exclusive_scan<G>(b2, gl, lane);
+    if (gl == 0) { p1[0] = 0.0; p2[0] = 0.0; }
+    for (int j = j0; j < j1; ++j) {
+        const double x = (double)s_lo[j];
+        r1 += x;
+        r2 += x * x;
+        p1[j + 1] = r1;
+        p2[j + 1] = r2;
+    }
+    // sums of the k highest up to the start of this lane's block of candidates k = j0+1 .. j1
+    b1 = 0.0;
+    b2 = 0.0;
+    for (int k = j0 + 1; k <= j1; ++k) {
+        const double x = (double)s_hi[m - k];
+        b1 += x;
+        b2 += x * x;
+    }
+    double u1 = run_exclusive_scan<G>(b1, gl, lane);
+    double u2 = run_exclusive_scan<G>(b2, gl, lane);
     __syncthreads();
 
     // ---- Alg. 2 steps 2-6: score every split k, keep the first strict maximum ----
-    // k = 0 (the m lowest) is the starting candidate; lane l of pass k0 scores k = k0 + l + 1.
     const double dm = (double)m;
-    double best = dm * c2 - c1 * c1;   // wave-uniform
-    int best_k = 0;
-    c1 = 0.0;
-    c2 = 0.0;
-    for (int k0 = 0; k0 < m; k0 += kWave) {
-        const int k = k0 + lane + 1;
-        const bool in = k <= m;
-        const float top = in ? s_val[n - k] : 0.0f;
+    double best = -__builtin_huge_val();
+    int best_k = 0x7fffffff;
+    if (gl == 0) {   // k = 0: the m lowest
+        best = dm * p2[m] - p1[m] * p1[m];
+        best_k = 0;
+    }
+    for (int k = j0 + 1; k <= j1; ++k) {
+        const float top = s_hi[m - k];
         const double x = (double)top;
-        const double u1 = wave_inclusive_scan(x) + c1;   // sum of the k highest
-        const double u2 = wave_inclusive_scan(x * x) + c2;
-        c1 = lane_value(u1, kWave - 1);
-        c2 = lane_value(u2, kWave - 1);
-        double D = -__builtin_huge_val();
-        if (in && top != s_val[m - k]) {   // else same multiset as split k-1
+        u1 += x;
+        u2 += x * x;
+        if (top != s_lo[m - k]) {   // else same multiset as split k-1
             const double S = p1[m - k] + u1;
             const double Q = p2[m - k] + u2;
-            D = dm * Q - S * S;
-        }
-        const double top_d = wave_max(D);
-        if (top_d > best) {   // strictly larger only: an earlier (smaller) k keeps its place on ties
-            best = top_d;
-            best_k = k0 + 1 + (int)__builtin_ctzll(__ballot(D == top_d));
+            const double D = dm * Q - S * S;
+            if (D > best) { best = D; best_k = k; }
         }
     }
+    run_best<G / 2>(best, best_k, lane);
 
     // ---- emit the (m-k) lowest then the k highest ----
     if (live) {
         int32_t* out = sel_idx + (size_t)group * m;
-        for (int j = lane; j < m; j += kWave)
-            out[j] = (j < m - best_k) ? (int32_t)s_idx[j] : (int32_t)s_idx[n - m + j];
-        if (sel_k != nullptr && lane == 0) sel_k[group] = best_k;
+        for (int j = gl; j < m; j += G) out[j] = (j < m - best_k) ? (int32_t)i_lo[j] : (int32_t)i_hi[j];
+        if (sel_k != nullptr && gl == 0) sel_k[group] = best_k;
     }
 }
 
-template <int KPL, int WAVES>
+template <int KPL, int G>
 pods_status launch_variant(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,
                            int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
-    const size_t lds = (size_t)WAVES * wave_lds_bytes(kWave * KPL, m);
+    constexpr int kGroupsPerWave = kWave / G;
+    const size_t per_wave = (size_t)kGroupsPerWave * group_lds_bytes(n, m, rule);
+    int waves = 4;                                  // as many waves per workgroup as keep its LDS within 64 KiB
+    while (waves > 1 && waves * per_wave > 64 * 1024) waves /= 2;
+    const size_t lds = waves * per_wave;
     if (lds > 160 * 1024) return fail(PODS_ERR_UNSUPPORTED, "pods_select: LDS need %zu B", lds);
-    auto kernel = select_kernel<KPL, WAVES>;
+    auto kernel = select_kernel<KPL, G>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -311,8 +388,8 @@ pods_status launch_variant(const float* rewards, const uint32_t* rand_keys, int3
             return fail(PODS_ERR_RUNTIME, "pods_select: cannot reserve %zu B of LDS: %s", lds,
                         hipGetErrorString(e));
     }
-    const unsigned grid = (unsigned)ceil_div(B, WAVES);
-    PODS_LAUNCH("pods_select", stream, kernel, dim3(grid), dim3(WAVES * kWave), lds, stream, rewards, rand_keys,
+    const unsigned grid = (unsigned)ceil_div(B, (int64_t)waves * kGroupsPerWave);
+    PODS_LAUNCH("pods_select", stream, kernel, dim3(grid), dim3(waves * kWave), lds, stream, rewards, rand_keys,
                 B, n, m, rule, sel_idx, sel_k);
     return check_launch("pods_select");
 }
@@ -321,13 +398,18 @@ pods_status launch_variant(const float* rewards, const uint32_t* rand_keys, int3
 
 pods_status launch_select(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,
                           int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
-    if (n <= 64) return launch_variant<1, 4>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
-    if (n <= 128) return launch_variant<2, 4>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
-    if (n <= 256) return launch_variant<4, 4>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
-    if (n <= 512) return launch_variant<8, 2>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
-    if (n <= 1024) return launch_variant<16, 2>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
-    if (n <= 2048) return launch_variant<32, 1>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
-    if (n <= 4096) return launch_variant<64, 1>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream);
+#define PODS_SELECT_VARIANT(KPL, G) \
+    return launch_variant<KPL, G>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream)
+    if (n <= 16) PODS_SELECT_VARIANT(4, 4);
+    if (n <= 32) PODS_SELECT_VARIANT(8, 4);
+    if (n <= 64) PODS_SELECT_VARIANT(16, 4);
+    if (n <= 128) PODS_SELECT_VARIANT(32, 4);
+    if (n <= 256) PODS_SELECT_VARIANT(32, 8);
+    if (n <= 512) PODS_SELECT_VARIANT(32, 16);
+    if (n <= 1024) PODS_SELECT_VARIANT(32, 32);
+    if (n <= 2048) PODS_SELECT_VARIANT(32, 64);
+    if (n <= 4096) PODS_SELECT_VARIANT(64, 64);
+#undef PODS_SELECT_VARIANT
     return fail(PODS_ERR_UNSUPPORTED, "pods_select: n = %d exceeds 4096", n);
 }
 
