@@ -15,7 +15,7 @@
 // row of 16 lanes has one), through the LDS crossbar (ds_swizzle) up to 32 lanes, by ds_bpermute
 // beyond.
 //
-// After the sort the m lowest and the m highest (reward, index) pairs of each group are staged in
+// After the sort the keys at the m lowest and the m highest positions of each group are staged in
 // LDS.  Each lane of the group then owns a contiguous block of the candidate splits k: it sums its
 // block of the lowest / highest rewards and their squares in double precision, a scan over the G
 // lanes turns block sums into block offsets, and the lane walks its candidates in ascending k,
@@ -189,6 +189,13 @@ __device__ __forceinline__ double run_exclusive_scan(double x, int gl, int lane)
     return gl == 0 ? 0.0 : __hiloint2double(hi, lo);
 }
 
+// The same sum taken from the other end of the run: over the lanes above this one.
+template <int G>
+__device__ __forceinline__ double run_exclusive_scan_down(double x, int gl, int lane) {
+    const double y = run_exclusive_scan<G>(lane_xor<G - 1>(x, lane), gl, lane);
+    return lane_xor<G - 1>(y, lane);
+}
+
 // Best (score, k) over the lanes of a run: the larger score, on equal scores the smaller k.
 template <int LM>
 __device__ __forceinline__ void run_best(double& best, int& best_k, int lane) {
@@ -200,34 +207,30 @@ __device__ __forceinline__ void run_best(double& best, int& best_k, int lane) {
     }
 }
 
-// Sorted positions [first, first + count) to LDS; this lane holds positions e0 .. e0 + KPL - 1, which
-// usually lie wholly inside or wholly outside the range.
+// Keys at sorted positions [first, first + count) to LDS; this lane holds positions e0 .. e0 + KPL - 1,
+// which usually lie wholly inside or wholly outside the range.
 template <int KPL>
-__device__ __forceinline__ void stage_range(const double (&key)[KPL], int e0, int first, int count,
-                                            float* vals, uint16_t* idxs) {
+__device__ __forceinline__ void stage_range(const double (&key)[KPL], int e0, int first, int count, double* dst) {
     if (e0 >= first && e0 + KPL <= first + count) {
 #pragma unroll
-        for (int j = 0; j < KPL; ++j) {
-            vals[e0 - first + j] = key_reward(key[j]);
-            idxs[e0 - first + j] = (uint16_t)key_index(key[j]);
-        }
+        for (int j = 0; j < KPL; ++j) dst[e0 - first + j] = key[j];
     } else if (e0 + KPL > first && e0 < first + count) {
 #pragma unroll
         for (int j = 0; j < KPL; ++j) {
             const int p = e0 + j;
-            if (p >= first && p < first + count) {
-                vals[p - first] = key_reward(key[j]);
-                idxs[p - first] = (uint16_t)key_index(key[j]);
-            }
+            if (p >= first && p < first + count) dst[p - first] = key[j];
         }
     }
 }
 
-// LDS per group.  Max-variance: float lo[m], hi[m]; uint16 ilo[m], ihi[m]; double p1[m+1], p2[m+1].
-// Other rules: uint16 idx[n].
-__host__ __device__ inline size_t group_lds_bytes(int n, int m, int rule) {
+constexpr int kBlockMax = 8;   // candidates per lane that the register-resident scan covers
+
+// LDS per group.  Max-variance: the keys at the m lowest and the m highest sorted positions, then,
+// when a lane owns more than kBlockMax candidates, double p1[m+1], p2[m+1].  Other rules: uint16 idx[n].
+__host__ __device__ inline size_t group_lds_bytes(int n, int m, int rule, int G) {
     if (rule != PODS_RULE_MAXVAR) return ((size_t)n * 2 + 15) / 16 * 16;
-    return ((size_t)m * 12 + 15) / 16 * 16 + 2 * (size_t)(m + 1) * 8;
+    const bool in_registers = (m + G - 1) / G <= kBlockMax;
+    return (size_t)m * 16 + (in_registers ? 0 : 2 * (size_t)(m + 1) * 8);
 }
 
 template <int KPL, int G>
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ r
     uint32_t sign = 0u;
     sort_from<KPL, G, 2>(key, sign, lane);
 
-    unsigned char* base = lds_raw + (size_t)slot * group_lds_bytes(n, m, rule);
+    unsigned char* base = lds_raw + (size_t)slot * group_lds_bytes(n, m, rule, G);
     if (rule != PODS_RULE_MAXVAR) {
         // Sec. 3.2's other rules are positions of the sorted order: the m highest (max-reward), the
         // (j + 1/2)/m quantiles taken as position floor((2j + 1) n / (2m)) (percentile), and the m
@@ -300,65 +303,119 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ r
         return;
     }
 
-    float* s_lo = reinterpret_cast<float*>(base);                 // rewards at positions 0 .. m-1
-    float* s_hi = s_lo + m;                                       // rewards at positions n-m .. n-1
-    uint16_t* i_lo = reinterpret_cast<uint16_t*>(s_hi + m);
-    uint16_t* i_hi = i_lo + m;
-    double* p1 = reinterpret_cast<double*>(base + ((size_t)m * 12 + 15) / 16 * 16);
+    double* k_lo = reinterpret_cast<double*>(base);   // keys at positions 0 .. m-1
+    double* k_hi = k_lo + m;                          // keys at positions n-m .. n-1
+    double* p1 = k_hi + m;
     double* p2 = p1 + (m + 1);
-    stage_range<KPL>(key, e0, 0, m, s_lo, i_lo);
-    stage_range<KPL>(key, e0, n - m, m, s_hi, i_hi);
+    stage_range<KPL>(key, e0, 0, m, k_lo);
+    stage_range<KPL>(key, e0, n - m, m, k_hi);
     __syncthreads();
 
-    // ---- Theorem 1: prefix sums of r and r^2 over the m lowest; lane gl owns positions [j0, j1) ----
+    // ---- Theorem 1 and Alg. 2 steps 2-6 ----
+    // Lane gl scores the candidates k = j0+1 .. j1.  Candidate k reads sorted positions m-k of the low
+    // and of the high staged range (the reward that leaves, the reward that enters), so the lane owns
+    // offsets [a, b) = [m-j1, m-j0) of both ranges.
     const int per_lane = (m + G - 1) / G;
     const int j0 = min(m, gl * per_lane), j1 = min(m, j0 + per_lane);
-    double b1 = 0.0, b2 = 0.0;
-    for (int j = j0; j < j1; ++j) {
-        const double x = (double)s_lo[j];
-        b1 += x;
-        b2 += x * x;
-    }
-    double r1 = run_exclusive_scan<G>(b1, gl, lane);
-    double r2 = run_exclusive_scan<G>(b2, gl, lane);
-    if (gl == 0) { p1[0] = 0.0; p2[0] = 0.0; }
-    for (int j = j0; j < j1; ++j) {
-        const double x = (double)s_lo[j];
-        r1 += x;
-        r2 += x * x;
-        p1[j + 1] = r1;
-        p2[j + 1] = r2;
-    }
-    // sums of the k highest up to the start of this lane's block of candidates k = j0+1 .. j1
-    b1 = 0.0;
-    b2 = 0.0;
-    for (int k = j0 + 1; k <= j1; ++k) {
-        const double x = (double)s_hi[m - k];
-        b1 += x;
-        b2 += x * x;
-    }
-    double u1 = run_exclusive_scan<G>(b1, gl, lane);
-    double u2 = run_exclusive_scan<G>(b2, gl, lane);
-    __syncthreads();
-
-    // ---- Alg. 2 steps 2-6: score every split k, keep the first strict maximum ----
     const double dm = (double)m;
     double best = -__builtin_huge_val();
     int best_k = 0x7fffffff;
-    if (gl == 0) {   // k = 0: the m lowest
-        best = dm * p2[m] - p1[m] * p1[m];
-        best_k = 0;
-    }
-    for (int k = j0 + 1; k <= j1; ++k) {
-        const float top = s_hi[m - k];
-        const double x = (double)top;
-        u1 += x;
-        u2 += x * x;
-        if (top != s_lo[m - k]) {   // else same multiset as split k-1
-            const double S = p1[m - k] + u1;
-            const double Q = p2[m - k] + u2;
-            const double D = dm * Q - S * S;
-            if (D > best) { best = D; best_k = k; }
+    if (per_lane <= kBlockMax) {
+        // Everything in registers: the block's rewards, its prefix sums of the low range (ascending
+        // position) and its running sums of the high range (ascending k, i.e. descending position).
+        const int a = m - j1, cnt = j1 - j0;
+        double lo_r[kBlockMax], hi_r[kBlockMax];
+#pragma unroll
+        for (int i = 0; i < kBlockMax; ++i) {
+            const int pos = min(a + i, m - 1);   // slots past the block are read in bounds and not used
+            lo_r[i] = (i < cnt) ? (double)key_reward(k_lo[pos]) : 0.0;
+            hi_r[i] = (i < cnt) ? (double)key_reward(k_hi[pos]) : 0.0;
+        }
+        double bl1 = 0.0, bl2 = 0.0, bh1 = 0.0, bh2 = 0.0;
+#pragma unroll
+        for (int i = 0; i < kBlockMax; ++i) {
+            bl1 += lo_r[i];
+            bl2 += lo_r[i] * lo_r[i];
+        }
+#pragma unroll
+        for (int i = kBlockMax - 1; i >= 0; --i) {
+            bh1 += hi_r[i];
+            bh2 += hi_r[i] * hi_r[i];
+        }
+        // lower positions of the low range belong to the lanes above; smaller k to the lanes below
+        double r1 = run_exclusive_scan_down<G>(bl1, gl, lane);
+        double r2 = run_exclusive_scan_down<G>(bl2, gl, lane);
+        double u1 = run_exclusive_scan<G>(bh1, gl, lane);
+        double u2 = run_exclusive_scan<G>(bh2, gl, lane);
+        double pp1[kBlockMax], pp2[kBlockMax];   // sums of the low range below position a + i
+#pragma unroll
+        for (int i = 0; i < kBlockMax; ++i) {
+            pp1[i] = r1;
+            pp2[i] = r2;
+            r1 += lo_r[i];
+            r2 += lo_r[i] * lo_r[i];
+        }
+        if (gl == 0) {   // k = 0, the m lowest: lane 0's block ends at position m
+            best = dm * r2 - r1 * r1;
+            best_k = 0;
+        }
+#pragma unroll
+        for (int i = kBlockMax - 1; i >= 0; --i) {   // ascending k = m - (a + i)
+            u1 += hi_r[i];
+            u2 += hi_r[i] * hi_r[i];
+            if (i < cnt && hi_r[i] != lo_r[i]) {   // else same multiset as split k-1
+                const double S = pp1[i] + u1;
+                const double Q = pp2[i] + u2;
+                const double D = dm * Q - S * S;
+                if (D > best) { best = D; best_k = m - (a + i); }
+            }
+        }
+    } else {
+        // Larger blocks: the prefix sums go through LDS.
+        double b1 = 0.0, b2 = 0.0;
+        for (int j = j0; j < j1; ++j) {
+            const double x = (double)key_reward(k_lo[j]);
+            b1 += x;
+            b2 += x * x;
+        }
+        double r1 = run_exclusive_scan<G>(b1, gl, lane);
+        double r2 = run_exclusive_scan<G>(b2, gl, lane);
+        if (gl == 0) { p1[0] = 0.0; p2[0] = 0.0; }
+        for (int j = j0; j < j1; ++j) {
+            const double x = (double)key_reward(k_lo[j]);
+            r1 += x;
+            r2 += x * x;
+            p1[j + 1] = r1;
+            p2[j + 1] = r2;
+        }
+        // sums of the k highest up to the start of this lane's block of candidates k = j0+1 .. j1
+        b1 = 0.0;
+        b2 = 0.0;
+        for (int k = j0 + 1; k <= j1; ++k) {
+            const double x = (double)key_reward(k_hi[m - k]);
+            b1 += x;
+            b2 += x * x;
+        }
+        double u1 = run_exclusive_scan<G>(b1, gl, lane);
+        double u2 = run_exclusive_scan<G>(b2, gl, lane);
+        __syncthreads();
+
+        // score every split k, keep the first strict maximum
+        if (gl == 0) {   // k = 0: the m lowest
+            best = dm * p2[m] - p1[m] * p1[m];
+            best_k = 0;
+        }
+        for (int k = j0 + 1; k <= j1; ++k) {
+            const float top = key_reward(k_hi[m - k]);
+            const double x = (double)top;
+            u1 += x;
+            u2 += x * x;
+            if (top != key_reward(k_lo[m - k])) {   // else same multiset as split k-1
+                const double S = p1[m - k] + u1;
+                const double Q = p2[m - k] + u2;
+                const double D = dm * Q - S * S;
+                if (D > best) { best = D; best_k = k; }
+            }
         }
     }
     run_best<G / 2>(best, best_k, lane);
@@ -366,7 +423,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ r
     // ---- emit the (m-k) lowest then the k highest ----
     if (live) {
         int32_t* out = sel_idx + (size_t)group * m;
-        for (int j = gl; j < m; j += G) out[j] = (j < m - best_k) ? (int32_t)i_lo[j] : (int32_t)i_hi[j];
+        for (int j = gl; j < m; j += G) out[j] = (int32_t)key_index((j < m - best_k) ? k_lo[j] : k_hi[j]);
         if (sel_k != nullptr && gl == 0) sel_k[group] = best_k;
     }
 }
@@ -375,7 +432,7 @@ template <int KPL, int G>
 pods_status launch_variant(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,
                            int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
     constexpr int kGroupsPerWave = kWave / G;
-    const size_t per_wave = (size_t)kGroupsPerWave * group_lds_bytes(n, m, rule);
+    const size_t per_wave = (size_t)kGroupsPerWave * group_lds_bytes(n, m, rule, G);
     int waves = 4;                                  // as many waves per workgroup as keep its LDS within 64 KiB
     while (waves > 1 && waves * per_wave > 64 * 1024) waves /= 2;
     const size_t lds = waves * per_wave;
