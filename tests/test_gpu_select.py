@@ -68,6 +68,32 @@ def test_select_ragged_shapes(pods, n, m, B):
         _assert_select_parity(pods, r, m, exact_sample=0 if m * m > 20000 else 8)
 
 
+@pytest.mark.parametrize("n,m,B", [(16, 16, 19), (17, 5, 21), (32, 32, 18), (64, 32, 40), (64, 33, 40), (128, 32, 33),
+                                   (128, 33, 33), (256, 64, 70), (256, 65, 70), (256, 255, 9), (257, 128, 9),
+                                   (512, 128, 11), (512, 129, 11), (1024, 256, 5), (1024, 257, 5), (2048, 512, 3),
+                                   (2048, 513, 3), (4096, 512, 2), (4096, 513, 2)])
+def test_select_block_boundaries(pods, n, m, B):
+    """Sizes on both sides of every switch inside the kernel: lanes per group, keys per lane, the
+    register-resident candidate scan (at most 8 splits per lane) against the one through LDS, group
+    counts that leave part of the last wavefront and workgroup idle."""
+    rng = np.random.default_rng(n * 7 + m)
+    r = (rng.integers(0, 4, (B, n)) * 0.25 + (rng.random((B, n)) < 0.3) * rng.standard_normal((B, n)) * 0.01).astype(np.float32)
+    _assert_select_parity(pods, r, m, exact_sample=0 if m * n > 40000 else 4)
+
+
+def test_select_unaligned_rewards_pointer(pods):
+    """A rewards pointer that is only 4-byte aligned must take the scalar load path."""
+    r = inputs.rewards(3, B=512)
+    flat = torch.zeros(r.size + 1, dtype=torch.float32, device="cuda")
+    flat[1:] = torch.from_numpy(r).cuda().reshape(-1)
+    view = flat[1:].view(r.shape)
+    assert view.data_ptr() % 16 == 4 and view.is_contiguous()
+    idx, k = pods.pods_select(view, 64)
+    torch.cuda.synchronize()
+    ridx, rk, _ = fast.select(r, 64)
+    assert np.array_equal(idx.cpu().numpy(), ridx) and np.array_equal(k.cpu().numpy(), rk)
+
+
 def test_select_is_deterministic(pods):
     r = inputs.rewards(3, B=4096)
     a = _gpu_select(pods, r, 64)
