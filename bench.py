@@ -143,6 +143,32 @@ def time_selector(lib, torch, inputs, steps):
                               bytes_per_launch=bytes_per_group * B, bytes_per_group=bytes_per_group))
 
 
+def time_gather(lib, torch, steps):
+    """pods_gather_rows on 4096 prompt groups of 64 rollouts, 16 kept, 4 KiB records (token ids at
+    T = 1024): 1 GiB of source records, 256 MiB read and 256 MiB written per launch."""
+    import numpy as np
+    B, n, m, row = 4096, 64, 16, 1024
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    src = torch.randint(0, 150000, (B, n, row), generator=g, device="cuda", dtype=torch.int32)
+    sel = torch.stack([torch.randperm(n, generator=g, device="cuda")[:m] for _ in range(64)]).to(torch.int32)
+    sel = sel.repeat(B // 64, 1).contiguous()
+    dst = torch.empty((B * m, row), dtype=torch.int32, device="cuda")
+    lib.pods_gather_rows(src, sel, dst)
+    torch.cuda.synchronize()
+    lib.pods_profile_enable(True)
+    for _ in range(max(steps, 5)):
+        lib.pods_gather_rows(src, sel, dst)
+    prof = lib.pods_profile_read()
+    lib.pods_profile_enable(False)
+    ms = float(np.mean([t for _, t in prof]))
+    nbytes = 2 * B * m * row * 4 + B * m * 4
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return dict(workload="B=4096 n=64 m=16, 4 KiB records", ms_per_launch=ms, launches=len(prof),
+                roofline=dict(bound="hbm", achieved=gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=gbs / PEAK_HBM_GBS,
+                              traffic=None, bytes_per_launch=nbytes))
+
+
 def cpu_selector(inputs):
     from oracle import fast
     r = inputs.rewards(3)
@@ -301,6 +327,7 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
         "selector": selector,
+        "gather": time_gather(lib, torch, args.steps),
         "loss": loss_val,
     }
     if not args.no_cpu_baseline:

@@ -8,6 +8,7 @@
  *                             (Sec. 3.3: definition, Lemma 3.1, Algorithm 2, Theorem 1)
  *   pods_downsample           the same selection step under any of the paper's rules: max-variance,
  *                             max-reward, percentile, random (Sec. 3.2)
+ *   pods_gather_rows          the kept rollouts' records, concatenated over prompts (Sec. 3.2)
  *   pods_advantage            group-normalised advantages over the kept rollouts (Sec. 3.2)
  *   pods_advantage_before     the "Before" variant: statistics from all n rollouts of the group
  *                             (App. "On Advantage Normalization")
@@ -120,6 +121,20 @@ pods_status pods_advantage(const float* rewards, const int32_t* sel_idx, int32_t
 pods_status pods_advantage_before(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
                                   int32_t m, float std_eps, float* adv, void* stream);
 
+/* The kept rollouts of every prompt, concatenated (Sec. 3.2: the same procedure per prompt, then
+ * the down-sampled rollouts are concatenated; Algorithm 1 steps 3-4).  Copies one fixed-size record
+ * per kept rollout (its token ids, old log-probs, length, ...) into the [R, ...] layout the token
+ * loss reads:  dst[(b*m + j) * row_bytes ...] = src[(b*n + sel_idx[b, j]) * row_bytes ...].
+ *
+ *   src        [B, n, row_bytes] bytes, in
+ *   sel_idx    [B, m] int32, in (values in [0, n); not checked)
+ *   dst        [B*m, row_bytes] bytes, out; must not overlap src
+ *   row_bytes  > 0.  Rows are copied 16 bytes per lane when src, dst and row_bytes are multiples
+ *              of 16, 4 bytes per lane when they are multiples of 4, else byte by byte.
+ */
+pods_status pods_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,
+                             size_t row_bytes, void* dst, void* stream);
+
 /* Bytes of workspace grpo_token_loss_fwd_bwd wants for these sizes (a recommendation: any
  * workspace of at least grpo_token_loss_workspace_min_bytes works, a larger one lets the
  * backward pass use larger vocabulary chunks).  Returns 0 for invalid sizes. */
@@ -163,6 +178,18 @@ pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const 
                                     float clip_eps, float grad_scale, float* loss, float* logp_out,
                                     float* d_hidden, float* d_w_lm, void* workspace,
                                     size_t workspace_bytes, void* stream);
+
+/* The same, for gradient accumulation over several rollout batches (App., "Note on gradient
+ * accumulation": a prompt's rollouts arrive in batches, each is down-sampled and back-propagated
+ * on its own): d_w_lm is read and the gradient is added to it; everything else is as above.
+ * The caller zeroes d_w_lm before the first batch of an accumulation. */
+pods_status grpo_token_loss_fwd_bwd_accumulate(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                               const float* old_logp, const float* adv,
+                                               const int32_t* lengths, int32_t R, int32_t T, int32_t d,
+                                               int32_t V, pods_dtype dt, float clip_eps, float grad_scale,
+                                               float* loss, float* logp_out, float* d_hidden,
+                                               float* d_w_lm, void* workspace, size_t workspace_bytes,
+                                               void* stream);
 
 /* Per-launch timing for benchmarks (not part of the method).  pods_profile_enable(1) makes every
  * later library call on this thread bracket each of its kernel launches with a pair of HIP events

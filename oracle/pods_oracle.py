@@ -22,6 +22,7 @@ What each function follows:
 * ``advantage``                a_{S,i} = (r_i - mu_S) / sigma_S over the kept rollouts (Sec. 3.2).
 * ``advantage_before``         the "Before" variant of App. "On Advantage Normalization": mean and
                                standard deviation from all n rollouts of the group.
+* ``gather_kept``              the kept rollouts of every prompt, concatenated (Sec. 3.2).
 * ``grpo_token_loss``          L_PODS (Sec. 3.2) with the policy's last layer written out
                                (logits = hidden . W_lm^T, softmax over the vocabulary), returned
                                as loss = -L_PODS with its analytic gradient w.r.t. hidden and W_lm.
@@ -192,6 +193,18 @@ def advantage(rewards: np.ndarray, sel_idx: np.ndarray, std_eps: float = 0.0) ->
         mu = x.sum() / m
         sigma = np.sqrt(((x - mu) ** 2).sum() / m)
         out[b] = (x - mu) / (sigma + std_eps)
+    return out
+
+
+def gather_kept(per_rollout: np.ndarray, sel_idx: np.ndarray) -> np.ndarray:
+    """Concatenation of the kept rollouts over a batch of prompts (Sec. 3.2; Alg. 1 steps 3-4):
+    per_rollout[B, n, ...] (any per-rollout record: token ids, old log-probs, lengths, ...) and
+    sel_idx[B, m] -> out[B*m, ...] with out[b*m + j] = per_rollout[b, sel_idx[b, j]]."""
+    B, m = sel_idx.shape
+    out = np.empty((B * m,) + per_rollout.shape[2:], dtype=per_rollout.dtype)
+    for b in range(B):
+        for j in range(m):
+            out[b * m + j] = per_rollout[b, sel_idx[b, j]]
     return out
 
 

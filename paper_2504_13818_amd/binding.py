@@ -11,6 +11,7 @@ _lib = None
 PODS_F32, PODS_BF16 = 0, 1
 PODS_RULE_MAXVAR, PODS_RULE_MAXR, PODS_RULE_PERC, PODS_RULE_RAND = 0, 1, 2, 3
 EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_advantage_before",
+                    "pods_gather_rows", "grpo_token_loss_fwd_bwd_accumulate",
                     "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
@@ -51,9 +52,13 @@ def load():
         f = getattr(lib, name)
         f.restype = _sz
         f.argtypes = [_i32, _i32, _i32, _i32, ctypes.c_int]
-    lib.grpo_token_loss_fwd_bwd.restype = ctypes.c_int
-    lib.grpo_token_loss_fwd_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
-                                            ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    for name in ("grpo_token_loss_fwd_bwd", "grpo_token_loss_fwd_bwd_accumulate"):
+        f = getattr(lib, name)
+        f.restype = ctypes.c_int
+        f.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
+                      ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.pods_gather_rows.restype = ctypes.c_int
+    lib.pods_gather_rows.argtypes = [_vp, _vp, _i32, _i32, _i32, _sz, _vp, _vp]
     lib.pods_profile_enable.restype = ctypes.c_int
     lib.pods_profile_enable.argtypes = [_i32]
     lib.pods_profile_count.restype = _i32
@@ -178,13 +183,34 @@ def grpo_token_loss_workspace_min_bytes(R, T, d, V, dt) -> int:
     return int(load().grpo_token_loss_workspace_min_bytes(R, T, d, V, dt))
 
 
+def pods_gather_rows(per_rollout, sel_idx, out=None, stream=None):
+    """per_rollout[B, n, ...] (any dtype, device) and sel_idx[B, m] int32 -> out[B*m, ...]: the kept
+    rollouts' records, concatenated over the prompts."""
+    import torch
+    _need(sel_idx, torch.int32, "sel_idx")
+    if not (isinstance(per_rollout, torch.Tensor) and per_rollout.is_cuda and per_rollout.is_contiguous()
+            and per_rollout.dim() >= 2):
+        raise TypeError("per_rollout: expected a contiguous CUDA tensor [B, n, ...]")
+    B, n = per_rollout.shape[:2]
+    m = sel_idx.shape[1]
+    row_bytes = per_rollout[0, 0].numel() * per_rollout.element_size() if per_rollout.dim() > 2 \
+        else per_rollout.element_size()
+    if out is None:
+        out = torch.empty((B * m,) + tuple(per_rollout.shape[2:]), dtype=per_rollout.dtype,
+                          device=per_rollout.device)
+    _check(load().pods_gather_rows(_ptr(per_rollout), _ptr(sel_idx), B, n, m, row_bytes, _ptr(out),
+                                   _stream(stream)))
+    return out
+
+
 def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_eps: float,
                             grad_scale: float = 1.0, workspace=None, want_logp: bool = True,
-                            out=None, stream=None):
+                            out=None, stream=None, accumulate_d_w: bool = False):
     """Returns dict(loss[1], logp[R, T] or None, d_hidden[R, T, d], d_w_lm[V, d]), float32 on device.
 
     `workspace` is a uint8 CUDA tensor (allocated at the recommended size when None); `out` may
-    carry preallocated loss / logp / d_hidden / d_w_lm tensors.
+    carry preallocated loss / logp / d_hidden / d_w_lm tensors.  With accumulate_d_w the gradient is
+    added to out["d_w_lm"] (grpo_token_loss_fwd_bwd_accumulate).
     """
     import torch
     dt = _dt(hidden)
@@ -198,6 +224,8 @@ def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_e
     R, T, d = hidden.shape
     V = w_lm.shape[0]
     dev = hidden.device
+    if accumulate_d_w and "d_w_lm" not in (out or {}):
+        raise ValueError("accumulate_d_w needs out['d_w_lm'] to accumulate into")
     out = dict(out or {})
     if "loss" not in out:
         out["loss"] = torch.empty((1,), dtype=torch.float32, device=dev)
@@ -210,7 +238,8 @@ def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_e
     if workspace is None:
         workspace = torch.empty((grpo_token_loss_workspace_bytes(R, T, d, V, dt),), dtype=torch.uint8,
                                 device=dev)
-    _check(load().grpo_token_loss_fwd_bwd(
+    entry = load().grpo_token_loss_fwd_bwd_accumulate if accumulate_d_w else load().grpo_token_loss_fwd_bwd
+    _check(entry(
         _ptr(hidden), _ptr(w_lm), _ptr(tokens), _ptr(old_logp), _ptr(adv), _ptr(lengths), R, T, d, V,
         dt, float(clip_eps), float(grad_scale), _ptr(out["loss"]), _ptr(out["logp"]),
         _ptr(out["d_hidden"]), _ptr(out["d_w_lm"]), _ptr(workspace), workspace.numel(),

@@ -2,6 +2,7 @@
 // mean and the population standard deviation of the m kept rewards of each prompt group; or, as
 // the "Before" variant of App. "On Advantage Normalization", with the statistics of all n
 // rewards of the group.  One wavefront per group; statistics are accumulated in double precision.
+// Also here: the copy that concatenates the kept rollouts' records (Sec. 3.2).
 #include "common.h"
 
 namespace pods {
@@ -59,7 +60,47 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void advantage_kernel(
     for (int j = lane; j < m; j += kWave) a[j] = (float)(((double)r[s[j]] - mu) * inv);
 }
 
+// Kept rollouts' records, concatenated over the prompts (Sec. 3.2).  blockIdx.x = output row
+// b*m + j, blockIdx.y = a slab of 1024 words of the row; W is the access word.
+template <typename W>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const W* __restrict__ src,
+                                                          const int32_t* __restrict__ sel_idx, int n, int m,
+                                                          size_t row_words, W* __restrict__ dst) {
+    const size_t out_row = blockIdx.x;
+    const size_t b = out_row / (size_t)m;
+    const size_t in_row = b * (size_t)n + (size_t)sel_idx[out_row];
+    const W* s = src + in_row * row_words;
+    W* d = dst + out_row * row_words;
+    constexpr int kPerThread = 4;
+    const size_t first = ((size_t)blockIdx.y * 256 * kPerThread) + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const size_t w = first + (size_t)i * 256;
+        if (w < row_words) d[w] = s[w];
+    }
+}
+
+template <typename W>
+void launch_gather_width(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,
+                         size_t row_bytes, void* dst, hipStream_t stream) {
+    const size_t row_words = row_bytes / sizeof(W);
+    const unsigned slabs = (unsigned)ceil_div((int64_t)row_words, 256 * 4);
+    PODS_LAUNCH("pods_gather_rows", stream, gather_rows_kernel<W>, dim3((unsigned)((int64_t)B * m), slabs), dim3(256),
+                0, stream, static_cast<const W*>(src), sel_idx, n, m, row_words, static_cast<W*>(dst));
+}
+
 }  // namespace
+
+pods_status launch_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,
+                               size_t row_bytes, void* dst, hipStream_t stream) {
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst) | row_bytes;
+    if (ceil_div((int64_t)row_bytes, 1024) > 65535)   // slabs of at least 1 KiB ride on grid.y
+        return fail(PODS_ERR_UNSUPPORTED, "pods_gather_rows: row_bytes = %zu exceeds 64 MiB", row_bytes);
+    if ((bits & 15) == 0) launch_gather_width<uint4>(src, sel_idx, B, n, m, row_bytes, dst, stream);
+    else if ((bits & 3) == 0) launch_gather_width<uint32_t>(src, sel_idx, B, n, m, row_bytes, dst, stream);
+    else launch_gather_width<uint8_t>(src, sel_idx, B, n, m, row_bytes, dst, stream);
+    return check_launch("pods_gather_rows");
+}
 
 pods_status launch_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
                              int32_t m, float std_eps, bool stats_from_all, float* adv, hipStream_t stream) {

@@ -140,11 +140,11 @@ size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int3
     return plan_loss(R, T, d, V, dt, 1).total;
 }
 
-pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const int32_t* tokens,
+static pods_status token_loss_entry(const void* hidden, const void* w_lm, const int32_t* tokens,
                                     const float* old_logp, const float* adv, const int32_t* lengths,
                                     int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
                                     float clip_eps, float grad_scale, float* loss, float* logp_out,
-                                    float* d_hidden, float* d_w_lm, void* workspace,
+                                    float* d_hidden, float* d_w_lm, bool accumulate_d_w, void* workspace,
                                     size_t workspace_bytes, void* stream) {
     if (hidden == nullptr || w_lm == nullptr || tokens == nullptr || old_logp == nullptr ||
         adv == nullptr || loss == nullptr || d_hidden == nullptr || d_w_lm == nullptr)
@@ -169,9 +169,43 @@ pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const 
     a.hidden = hidden; a.w_lm = w_lm; a.tokens = tokens; a.old_logp = old_logp; a.adv = adv;
     a.lengths = lengths; a.R = R; a.T = T; a.d = d; a.V = V; a.dt = dt; a.clip_eps = clip_eps;
     a.grad_scale = grad_scale; a.loss = loss; a.logp_out = logp_out; a.d_hidden = d_hidden;
-    a.d_w_lm = d_w_lm; a.workspace = static_cast<unsigned char*>(workspace);
+    a.d_w_lm = d_w_lm; a.accumulate_d_w = accumulate_d_w; a.workspace = static_cast<unsigned char*>(workspace);
     a.workspace_bytes = workspace_bytes; a.stream = static_cast<hipStream_t>(stream);
     return run_loss(a);
+}
+
+pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                    const float* old_logp, const float* adv, const int32_t* lengths,
+                                    int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
+                                    float clip_eps, float grad_scale, float* loss, float* logp_out,
+                                    float* d_hidden, float* d_w_lm, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    return token_loss_entry(hidden, w_lm, tokens, old_logp, adv, lengths, R, T, d, V, dt, clip_eps, grad_scale,
+                            loss, logp_out, d_hidden, d_w_lm, false, workspace, workspace_bytes, stream);
+}
+
+pods_status grpo_token_loss_fwd_bwd_accumulate(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                               const float* old_logp, const float* adv,
+                                               const int32_t* lengths, int32_t R, int32_t T, int32_t d,
+                                               int32_t V, pods_dtype dt, float clip_eps, float grad_scale,
+                                               float* loss, float* logp_out, float* d_hidden,
+                                               float* d_w_lm, void* workspace, size_t workspace_bytes,
+                                               void* stream) {
+    return token_loss_entry(hidden, w_lm, tokens, old_logp, adv, lengths, R, T, d, V, dt, clip_eps, grad_scale,
+                            loss, logp_out, d_hidden, d_w_lm, true, workspace, workspace_bytes, stream);
+}
+
+pods_status pods_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,
+                             size_t row_bytes, void* dst, void* stream) {
+    if (src == nullptr || sel_idx == nullptr || dst == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "pods_gather_rows: null pointer");
+    if (B <= 0 || n <= 0 || m <= 0 || row_bytes == 0)
+        return fail(PODS_ERR_INVALID_ARG, "pods_gather_rows: B=%d n=%d m=%d row_bytes=%zu must be positive", B, n, m,
+                    row_bytes);
+    if (m > n) return fail(PODS_ERR_INVALID_ARG, "pods_gather_rows: m=%d exceeds n=%d", m, n);
+    if ((int64_t)B * m > (int64_t)0x7fffffff)
+        return fail(PODS_ERR_UNSUPPORTED, "pods_gather_rows: more than 2^31 - 1 kept rollouts");
+    return launch_gather_rows(src, sel_idx, B, n, m, row_bytes, dst, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -25,6 +25,7 @@ struct LossArgs {
     float* logp_out;
     float* d_hidden;
     float* d_w_lm;
+    bool accumulate_d_w;   // d_w_lm += gradient instead of d_w_lm = gradient
     unsigned char* workspace;
     size_t workspace_bytes;
     hipStream_t stream;

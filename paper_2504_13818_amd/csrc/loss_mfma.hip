@@ -565,7 +565,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
 __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict__ hdr,
                                                     const uint16_t* __restrict__ h16,
                                                     const uint16_t* __restrict__ q, int64_t ldq,
-                                                    int d, int V, int v0, int vc,
+                                                    int d, int V, int v0, int vc, int accumulate,
                                                     float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
@@ -598,6 +598,7 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
                 f32x4 vv;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) vv[c] = acc[mi][ni][b * 4 + c] * scale;
+                if (accumulate) vv += *reinterpret_cast<const f32x4*>(row + k);
                 *reinterpret_cast<f32x4*>(row + k) = vv;
             }
     }
@@ -841,7 +842,8 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
                            kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(h16),
-                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, a.d_w_lm);
+                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, a.accumulate_d_w ? 1 : 0,
+                           a.d_w_lm);
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
     }
     PODS_LAUNCH("token loss d_w_lm (y logit)", a.stream, dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,

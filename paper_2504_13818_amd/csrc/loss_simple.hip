@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void simple_dw_kernel(const LossHeader* __rest
                                                         const float* __restrict__ g,
                                                         const E* __restrict__ hidden,
                                                         const E* __restrict__ w, int d, int V,
-                                                        float* __restrict__ d_w) {
+                                                        int accumulate, float* __restrict__ d_w) {
     extern __shared__ float lds[];
     float* ws = lds;            // [d]
     float* acc = lds + d;       // [d]
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void simple_dw_kernel(const LossHeader* __rest
         }
         __syncthreads();
     }
-    for (int k = threadIdx.x; k < d; k += 256) d_w[wrow + k] = acc[k];
+    for (int k = threadIdx.x; k < d; k += 256) d_w[wrow + k] = accumulate ? d_w[wrow + k] + acc[k] : acc[k];
 }
 
 template <typename K>
@@ -209,7 +209,7 @@ pods_status backward_t(const LossArgs& a, const LossPlan& p) {
     if ((st = check_launch("token loss d_hidden (plain)")) != PODS_OK) return st;
     PODS_LAUNCH("token loss d_w_lm (plain)", a.stream, kdw, dim3((unsigned)a.V), dim3(256), lds, a.stream, hdr, row_map, tok, lse, g,
                        static_cast<const E*>(a.hidden), static_cast<const E*>(a.w_lm), a.d, a.V,
-                       a.d_w_lm);
+                       a.accumulate_d_w ? 1 : 0, a.d_w_lm);
     return check_launch("token loss d_w_lm (plain)");
 }
 

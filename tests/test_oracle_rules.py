@@ -159,3 +159,16 @@ def test_before_hand_worked_and_relations():
     # constant group -> zeros; eps enters the denominator
     assert np.array_equal(po.advantage_before(np.full((1, 5), 0.3, np.float32), np.array([[1, 2]], np.int32)), [[0, 0]])
     assert np.allclose(po.advantage_before(r, sel, std_eps=2.0), [[-0.75, 1.0, 0.0]])
+
+
+# ---- concatenation of the kept rollouts ------------------------------------------------------
+
+def test_gather_kept_is_fancy_indexing():
+    rng = np.random.default_rng(9)
+    B, n, m = 5, 7, 3
+    rec = rng.integers(0, 1000, (B, n, 4)).astype(np.int32)
+    sel = np.stack([rng.choice(n, m, replace=False) for _ in range(B)]).astype(np.int32)
+    want = rec[np.arange(B)[:, None], sel].reshape(B * m, 4)          # library indexing
+    assert np.array_equal(po.gather_kept(rec, sel), want)
+    lens = rng.integers(0, 50, (B, n)).astype(np.int32)              # one scalar per rollout
+    assert np.array_equal(po.gather_kept(lens, sel), np.take_along_axis(lens, sel.astype(np.int64), axis=1).reshape(-1))
