@@ -340,20 +340,22 @@ __device__ __forceinline__ int acc_slot_of(int rel) {
 // token, one partial per vocabulary tile, merged later by the surrogate kernel; and z_y.
 // One tile per workgroup (rather than a workgroup walking many vocabulary tiles) keeps the 32
 // workgroups of an XCD in step, which is what lets them share operand tiles in the 4 MiB L2.
+// A launch covers vocabulary tiles vt0 .. vt0 + nvt_launch - 1.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restrict__ hdr,
                                                      const int32_t* __restrict__ tok,
                                                      const uint16_t* __restrict__ ht,
                                                      const uint16_t* __restrict__ wt,
-                                                     int d, int V, int64_t slot_stride,
+                                                     int d, int V, int vt0, int nvt_launch,
+                                                     int64_t slot_stride,
                                                      float* __restrict__ pmax, float* __restrict__ psum,
                                                      float* __restrict__ zy) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
-    const int nvt = (V + kTile - 1) / kTile;
     int64_t tt, vt;
-    if (!decode_tile(blockIdx.x, ntt, nvt, tt, vt)) return;
+    if (!decode_tile(blockIdx.x, ntt, nvt_launch, tt, vt)) return;
+    vt += vt0;
     const LaneGeom g = lane_geom();
     const int KT = d / kBK;
 
@@ -787,12 +789,20 @@ pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
     if ((st = check_launch("transpose H")) != PODS_OK) return st;
     const int64_t ntt = p.ncap_ld / kTile;
     const int64_t nvt = p.vld_t / kTile;
-    PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nvt)), dim3(256),
-                kLdsBytes, a.stream, hdr, reinterpret_cast<const int32_t*>(ws + p.off_tok),
-                reinterpret_cast<const uint16_t*>(ht), reinterpret_cast<const uint16_t*>(wt), a.d, a.V, p.ncap_ld,
-                reinterpret_cast<float*>(ws + p.off_pmax), reinterpret_cast<float*>(ws + p.off_psum),
-                reinterpret_cast<float*>(ws + p.off_zy));
-    return check_launch("token loss forward");
+    // One launch per kDefaultVocabChunk columns: the chunk of W then stays in the Infinity Cache while the
+    // token tiles stream past it (one launch over the whole vocabulary re-reads W from HBM for every
+    // block of token tiles and measured 6 % slower).
+    const int64_t step_vt = kDefaultVocabChunk / kTile;
+    for (int64_t vt0 = 0; vt0 < nvt; vt0 += step_vt) {
+        const int64_t nl = nvt - vt0 < step_vt ? nvt - vt0 : step_vt;
+        PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nl)), dim3(256),
+                    kLdsBytes, a.stream, hdr, reinterpret_cast<const int32_t*>(ws + p.off_tok),
+                    reinterpret_cast<const uint16_t*>(ht), reinterpret_cast<const uint16_t*>(wt), a.d, a.V, (int)vt0,
+                    (int)nl, p.ncap_ld, reinterpret_cast<float*>(ws + p.off_pmax),
+                    reinterpret_cast<float*>(ws + p.off_psum), reinterpret_cast<float*>(ws + p.off_zy));
+        if ((st = check_launch("token loss forward")) != PODS_OK) return st;
+    }
+    return PODS_OK;
 }
 
 pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
