@@ -49,6 +49,8 @@ constexpr int kStageBytes = 2 * kOperandBytes;     // A then B
 constexpr int kStages = 4;                         // ring of LDS stages
 constexpr int kDist = kStages - 1;                 // k-tiles in flight ahead of the one being multiplied
 constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
+constexpr int kQPitch = 2 * kTile + 8;             // bytes per token row of the q tile staged in LDS
+constexpr int kRecomputeLdsBytes = kTile * kQPitch > kLdsBytes ? kTile * kQPitch : kLdsBytes;   // 130 KiB
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kInvLogitScale = 1.0f / (kWScale * kHScale);   // logits are accumulated as kWScale kHScale z
 constexpr int kXcds = 8;
@@ -467,14 +469,20 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
     zero_acc(acc);
     k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
 
-    const int vloc = (int)vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // chunk-local row of (mi=0, r=0)
-    const int vbase = v0 + vloc;
+    const int vtile = g.wm * 128 + 4 * (g.lane >> 5);        // tile-local vocabulary row of (mi=0, r=0)
+    const int vbase = v0 + (int)vt * kTile + vtile;
     const bool partial = (v0 + (int)vt * kTile + kTile > V);
     constexpr float kLog2Q = 14.0f;
     static_assert(kQScale == 16384.0f, "kLog2Q must be log2(kQScale)");
+    // The q tile goes to memory through LDS: a lane holds 4 consecutive vocabulary entries of one token,
+    // so storing from registers would scatter 8-byte pieces over 32 token rows per instruction; staged
+    // as [token][vocabulary] rows (pitch 520 B: the 32 rows a half-wave writes fall into 32 different
+    // bank pairs) every later store instruction covers two whole 512-byte rows.
+    __builtin_amdgcn_s_barrier();   // every wave has left the operand ring
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
-        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+        const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
+        const int64_t p = tt * kTile + tloc;
         const bool valid = p < n_valid;
         const int y = valid ? tok[p] : -1;
         // kQScale softmax = 2^(z log2e - lse log2e + 14); rows past N get 2^-inf = 0
@@ -500,6 +508,7 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
                 for (int r = 0; r < 16; ++r)
                     if (vbase + mi * 32 + 8 * (r >> 2) + (r & 3) >= V) val[mi][r] = 0.0f;
         }
+        unsigned char* row = lds + tloc * kQPitch + vtile * 2;
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
@@ -507,9 +516,20 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
                 f16x4 pk;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) pk[c] = (_Float16)val[mi][b * 4 + c];
-                const int vl = vloc + mi * 32 + 8 * b;
-                *reinterpret_cast<f16x4*>(q + p * ldq + vl) = pk;
+                *reinterpret_cast<f16x4*>(row + (mi * 32 + 8 * b) * 2) = pk;
             }
+    }
+    __syncthreads();
+    // wave w stores token rows 64 w .. 64 w + 63 of the tile, two rows (2 x 512 B) per instruction
+    _Float16* qtile = q + (tt * kTile) * ldq + vt * kTile;
+#pragma unroll 4
+    for (int i = 0; i < 32; ++i) {
+        const int r = g.wave * 64 + 2 * i + (g.lane >> 5);
+        const unsigned char* src = lds + r * kQPitch + (g.lane & 31) * 16;
+        const f16x4 lo = *reinterpret_cast<const f16x4*>(src);
+        const f16x4 hi = *reinterpret_cast<const f16x4*>(src + 8);
+        const f16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        *reinterpret_cast<f16x8*>(qtile + (int64_t)r * ldq + (g.lane & 31) * 8) = both;
     }
 }
 
@@ -762,8 +782,8 @@ __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restri
     *reinterpret_cast<f16x8*>(dst + r * d + k) = out;
 }
 
-pods_status reserve(const void* kernel, const char* what) {
-    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+pods_status reserve(const void* kernel, const char* what, int bytes = kLdsBytes) {
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return fail(PODS_ERR_RUNTIME, "%s: cannot reserve LDS: %s", what, hipGetErrorString(e));
     return PODS_OK;
 }
@@ -821,7 +841,7 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
     const auto* hidden = static_cast<const uint16_t*>(a.hidden);
     const auto* w = static_cast<const uint16_t*>(a.w_lm);
     pods_status st;
-    if ((st = reserve(reinterpret_cast<const void*>(recompute_kernel), "token loss recompute")) != PODS_OK) return st;
+    if ((st = reserve(reinterpret_cast<const void*>(recompute_kernel), "token loss recompute", kRecomputeLdsBytes)) != PODS_OK) return st;
     if ((st = reserve(reinterpret_cast<const void*>(dh_kernel), "token loss d_hidden")) != PODS_OK) return st;
     if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
 
@@ -844,7 +864,7 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
         const int v0 = c * p.vc;
         if (v0 >= a.V) break;
         PODS_LAUNCH("token loss recompute", a.stream, recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
-                           kLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, p.ldq, dz);
+                           kRecomputeLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, p.ldq, dz);
         if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
                            a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
