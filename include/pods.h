@@ -170,7 +170,8 @@ size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int3
  * fp32.  For the two gradient contractions the softmax part of the per-logit gradient is rounded
  * to fp16 (scaled so that it cannot overflow) and the generated token's own logit is applied in
  * fp32; results are deterministic (no floating-point atomics).  A bf16 call with d not a multiple
- * of 64, and every fp32 call, uses plain fp32 vector arithmetic throughout.  d <= 16384.
+ * of 64, and every fp32 call, uses plain fp32 vector arithmetic throughout.  d <= 16384, R*T <= 2^30,
+ * T <= 16776960 (PODS_ERR_UNSUPPORTED beyond).
  */
 pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const int32_t* tokens,
                                     const float* old_logp, const float* adv, const int32_t* lengths,

@@ -159,6 +159,7 @@ static pods_status token_loss_entry(const void* hidden, const void* w_lm, const 
     if (!loss_sizes_ok(R, T, d, V, dt))
         return fail(PODS_ERR_UNSUPPORTED, "grpo_token_loss_fwd_bwd: R*T exceeds 2^30 positions");
     if (d > 16384) return fail(PODS_ERR_UNSUPPORTED, "grpo_token_loss_fwd_bwd: d=%d exceeds 16384", d);
+    if (T > 65535 * 256) return fail(PODS_ERR_UNSUPPORTED, "grpo_token_loss_fwd_bwd: T=%d exceeds 16776960", T);
     if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
         return fail(PODS_ERR_WORKSPACE, "grpo_token_loss_fwd_bwd: workspace null or not 256-byte aligned");
     const size_t need = plan_loss(R, T, d, V, dt, 1).total;

@@ -119,8 +119,8 @@ __global__ __launch_bounds__(256) void fill_rows_kernel(const int32_t* __restric
                                                         int32_t* __restrict__ row_map,
                                                         int32_t* __restrict__ tok,
                                                         float* __restrict__ logp_out) {
-    const int i = blockIdx.y;
-    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x;                       // rollouts ride on grid.x (no 65535 limit)
+    const int t = blockIdx.y * 256 + threadIdx.x;
     if (t >= T) return;
     const int len = lengths ? lengths[i] : T;
     const int64_t flat = (int64_t)i * T + t;
@@ -241,7 +241,7 @@ pods_status run_loss(const LossArgs& a) {
     PODS_LAUNCH("scan_lengths", a.stream, scan_lengths_kernel, dim3(1), dim3(1024), 0, a.stream, a.lengths, a.R, a.T,
                        offsets, hdr);
     if ((st = check_launch("scan_lengths")) != PODS_OK) return st;
-    PODS_LAUNCH("fill_rows", a.stream, fill_rows_kernel, dim3((unsigned)ceil_div(a.T, 256), (unsigned)a.R), dim3(256),
+    PODS_LAUNCH("fill_rows", a.stream, fill_rows_kernel, dim3((unsigned)a.R, (unsigned)ceil_div(a.T, 256)), dim3(256),
                        0, a.stream, a.lengths, a.tokens, offsets, a.T, row_map, tok, a.logp_out);
     if ((st = check_launch("fill_rows")) != PODS_OK) return st;
     if (a.lengths != nullptr) {

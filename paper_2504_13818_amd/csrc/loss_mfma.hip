@@ -1,17 +1,18 @@
 // Matrix-core kernels for the GRPO-PODS token loss with bf16 inputs (gfx950).
 //
-// All four contractions of the update are "NT" products C[i][j] = sum_k A[i][k] B[j][k] with both
-// operands contiguous along k, computed by one workgroup per 256x256 output tile with
-// v_mfma_f32_32x32x16_bf16 and fp32 accumulators:
+// All four contractions of the update run as one workgroup per 256x256 output tile with
+// v_mfma_f32_32x32x16_f16 and fp32 accumulators, on fp16 working copies of the bf16 inputs (exact
+// while the scaled value stays in fp16's normal range):
 //
-//   forward    z[v][t]  = sum_k W[v][k]   H[t][k]       -> running (max, sum exp) per token, z_y
+//   forward    z[v][t]  = sum_k Wt[k][v]  Ht[k][t]      -> (max, sum exp) per token and vocabulary tile, z_y
 //   recompute  z[v][t]  (same)                          -> q = 2^14 exp(z - lse) as fp16 (0 at v = y)
-//   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times g_t, accumulated over vocab chunks
+//   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times -g_t, accumulated over vocab chunks
 //   d_w_lm     dW[k][v] = sum_t H16[t][k] q[t][v]       -> complete per vocabulary chunk
 //
-// An operand whose contraction index is its row index in memory (W16 in d_hidden, both operands
-// in d_w_lm) is staged in LDS as it lies in memory and read with the transposing LDS load, so q is
-// stored once (token-major) and no transposed copy of any matrix exists.
+// An operand whose contraction index is its row index in memory (all of them except q in
+// d_hidden) is staged in LDS as it lies in memory and read with the transposing LDS load, so q is
+// stored once (token-major) and no transposed copy of q or of the gradient operands exists; the
+// logits read blocked transposed copies Wt, Ht made once per call.
 //
 // The per-logit gradient is dz = -g_t q / 2^14 for v != y.  q is kept in fp16 (11-bit significand)
 // rather than bf16 (8-bit) so that a logit with a large probability does not carry a 2^-8 error
@@ -21,14 +22,15 @@
 // The generated token's own logit, dz_y = g (1 - softmax_y), dominates each token's gradient and
 // is kept out of the rounded operands altogether: its two rank-one terms, dz_y W_y into d_hidden
 // and dz_y h_t into row y of d_w_lm, are added in fp32 by two small kernels (exact bf16 products,
-// fixed summation order, no atomics).  The first
-// operand ("A role") indexes accumulator rows: a lane of the 32x32 MFMA result holds one column j
-// and rows 8b + 4(lane/32) + c, so the reduction over the vocabulary in the forward pass is
-// almost entirely inside a lane, and the gradient tiles store four consecutive k per lane.
+// fixed summation order, no atomics).
+//
+// The first operand ("A role") indexes accumulator rows: a lane of the 32x32 MFMA result holds one
+// column j and rows 8b + 4(lane/32) + c, so the reduction over the vocabulary in the forward pass
+// is almost entirely inside a lane, and the gradient tiles store four consecutive k per lane.
 //
 // Workgroup: 256 threads = 4 waves as 2x2, each wave a 128x128 sub-tile (4x4 MFMA blocks, 256
 // accumulator registers).  K is walked in tiles of 32 through a ring of four LDS stages of
-// (256 + 256) rows x 64 B, filled by direct-to-LDS global loads three tiles ahead (see k_loop).
+// 2 x 16 KiB, filled by direct-to-LDS global loads three tiles ahead (see k_loop).
 // Workgroup ids are mapped to tiles so that the 32 workgroups resident on one XCD (one L2) form a
 // 4 x 8 block of tiles and share operand rows.
 #include "loss.h"
@@ -36,7 +38,6 @@
 namespace pods {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -98,15 +99,13 @@ struct Operand {  // this thread's 4 source pointers (bytes) into one operand k-
 // 64 B.  Rows at or beyond `rows` are clamped to the last row (their products are masked or
 // multiplied by zeros by the caller).
 __device__ __forceinline__ void operand_rows(Operand& op, const uint16_t* base, int64_t ld,
-                                             int64_t row0, int64_t rows, int64_t col0,
-                                             const int32_t* __restrict__ gather) {
+                                             int64_t row0, int64_t rows, int64_t col0) {
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
     const int gc = (l & 3) ^ ((l >> 4) & 3);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int64_t row = row0 + 64 * i + 16 * w + (l >> 2);
         if (row >= rows) row = rows - 1;
-        if (gather != nullptr) row = gather[row];
         op.ptr[i] = reinterpret_cast<const unsigned char*>(base + row * ld + col0 + gc * 8);
     }
     op.step = 64;
@@ -167,9 +166,6 @@ __device__ __forceinline__ LaneGeom lane_geom() {
     return g;
 }
 
-__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
 __device__ __forceinline__ f32x16 mfma(f16x8 a, f16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
@@ -193,8 +189,8 @@ __device__ __forceinline__ E read_frag(const unsigned char* stage, int rd, int k
     }
 }
 
-// acc += A . B^T over KT k-tiles of 32.  E is the operand element vector (bf16x8 for the logits,
-// f16x8 for the gradient contractions); AKM / BKM say which operands are k-major (see Operand).
+// acc += A . B^T over KT k-tiles of 32.  E is the operand element vector (f16x8); AKM / BKM say
+// which operands are k-major (see Operand).
 //
 // Each k-tile (two MFMA k-steps) lives in one stage of a ring of kStages LDS stages; kDist tiles
 // are always in flight.  One iteration multiplies tile kt in two phases of 16 MFMAs:
@@ -553,7 +549,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     Operand A, B;
     operand_kmajor(A, w16, d, v0, kt0 * kTile, d);   // rows v >= V of W16 are zero
     // every row of the last token tile was written by the recompute step (zeros past N)
-    operand_rows(B, q, ldq, tt * kTile, ntt * kTile, 0, nullptr);
+    operand_rows(B, q, ldq, tt * kTile, ntt * kTile, 0);
     f32x16 acc[4][4];
     zero_acc(acc);
     const int vwidth = min(vc, (V - v0 + kTile - 1) / kTile * kTile);   // whole tiles that hold vocabulary

@@ -40,6 +40,22 @@ def test_bf16_tiny_and_tile_boundaries(pods, R, T, d, V):
     H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale, gemm_dtype=np.float64))
 
 
+def test_more_rollouts_than_one_grid_dimension(pods):
+    """R above 65535 (many short rollouts): nothing in the path may ride on a 16-bit grid dimension."""
+    R, T, d, V = 66000, 3, 64, 300
+    case = H.loss_case(4, R, T, d, V, sigma=0.2)
+    H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case))
+    # Every element of d_w_lm here is a sum of about 10^5 terms of random sign, so an element can be far
+    # smaller than its terms; at a scale where the absolute floor no longer helps, the fp16 rounding of
+    # the softmax operand is bounded against the size of the matrix, not of each element.
+    scale = float(R * max(case["lengths"].mean(), 1))
+    got, ref = H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale)
+    H.assert_close_tensor("logp", got["logp"], ref["logp"])
+    H.assert_close_tensor("d_hidden", got["d_hidden"], ref["d_hidden"])
+    assert np.abs(got["d_w"] - ref["d_w"]).max() <= H.RTOL * np.abs(ref["d_w"]).max()
+    assert np.linalg.norm(got["d_w"] - ref["d_w"]) <= H.RTOL * np.linalg.norm(ref["d_w"])
+
+
 def test_bf16_d_not_multiple_of_64_takes_plain_path(pods):
     case = H.loss_case(1, 3, 20, 96, 400, sigma=0.3)
     H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case, gemm_dtype=np.float64))
