@@ -136,8 +136,9 @@ pods_status pods_gather_rows(const void* src, const int32_t* sel_idx, int32_t B,
                              size_t row_bytes, void* dst, void* stream);
 
 /* Bytes of workspace grpo_token_loss_fwd_bwd wants for these sizes (a recommendation: any
- * workspace of at least grpo_token_loss_workspace_min_bytes works, a larger one lets the
- * backward pass use larger vocabulary chunks).  Returns 0 for invalid sizes. */
+ * workspace of at least grpo_token_loss_workspace_min_bytes works; below the recommendation the
+ * backward pass uses smaller vocabulary chunks, above it nothing changes).  Returns 0 for invalid
+ * sizes. */
 size_t grpo_token_loss_workspace_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
 size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
 

@@ -54,7 +54,21 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     };
     int vc;
     if (mode == 0) {
-        vc = (int)(vround < kDefaultVocabChunk ? vround : kDefaultVocabChunk);
+        // The d_w_lm launch of a chunk has (vc / 256) x ceil(d / 256) tiles of equal, long duration: pick
+        // the chunk, near the default, whose tile count fills whole rounds of the 256 CUs best
+        // (d = 3584: 36 x 14 = 504 tiles, not 32 x 14 = 448).
+        const int64_t nd = ((int64_t)d + kTile - 1) / kTile;
+        const int64_t nv0 = kDefaultVocabChunk / kTile;
+        int64_t best_nv = nv0;
+        double best_eff = -1.0;
+        for (int64_t nv = nv0 - nv0 / 4; nv <= nv0 + nv0 / 4; ++nv) {
+            const int64_t tiles = nv * nd;
+            const double eff = (double)tiles / (double)((tiles + 255) / 256 * 256);
+            const bool closer = llabs(nv - nv0) < llabs(best_nv - nv0);
+            if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && closer)) { best_eff = eff; best_nv = nv; }
+        }
+        const int64_t want = best_nv * kTile;
+        vc = (int)(vround < want ? vround : want);
     } else if (mode == 1) {
         vc = kTile;
     } else {
@@ -69,6 +83,9 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
         }
         vc = lo * kTile;
         if (vc > 4 * kDefaultVocabChunk) vc = 4 * kDefaultVocabChunk;
+        // a caller-given workspace at least as large as the recommendation gets the recommended chunk
+        LossPlan rec = plan_loss(R, T, d, V, dt, 0);
+        if (rec.total <= mode && rec.vc <= vc) vc = rec.vc;
     }
     total_for(vc, p);
     return p;

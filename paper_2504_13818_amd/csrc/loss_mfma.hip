@@ -55,7 +55,7 @@ constexpr int kRecomputeLdsBytes = kTile * kQPitch > kLdsBytes ? kTile * kQPitch
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kInvLogitScale = 1.0f / (kWScale * kHScale);   // logits are accumulated as kWScale kHScale z
 constexpr int kXcds = 8;
-constexpr int kSuper0 = 4, kSuper1 = 8;            // tiles per XCD block along the two tile axes
+constexpr int kSuper0 = 4, kSuper1 = 8;            // tiles per XCD block along the two tile axes (at most)
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
@@ -310,19 +310,48 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
 }
 
 // Workgroup id -> tile (t0, t1) of an n0 x n1 tile grid, so that ids congruent mod 8 (one XCD)
-// walk 4 x 8 blocks of tiles.  Returns false for ids that fall outside the grid.
+// walk blocks of 4 x s1 tiles (the 32 workgroups resident on an XCD then share operand rows in its L2).  s1 divides the second axis as evenly as blocks of at most 8 can
+// (14 tiles -> 7 + 7, not 8 + 6): with an even number of unequal block columns the short column would
+// always fall to the same XCDs, which then run out of work early.  Returns false for ids that fall
+// outside the grid.
+__host__ __device__ inline int64_t super_width(int64_t n1) {
+    const int64_t cols = (n1 + kSuper1 - 1) / kSuper1;
+    return (n1 + cols - 1) / cols;
+}
+// Blocks go round the XCDs (block b to XCD b mod 8), which keeps the XCDs on neighbouring blocks at any
+// time.  A launch with few blocks (d_w_lm: one or two rounds of long tiles) would leave the XCDs
+// unevenly loaded that way, so there each XCD takes one contiguous eighth of the slots (tiles, and the
+// holes of partial blocks) in block order instead: balanced to within one tile.
+constexpr int64_t kFewBlocks = 64;
+__host__ __device__ inline int64_t super_blocks(int64_t n0, int64_t n1) {
+    const int64_t s1 = super_width(n1);
+    return ((n0 + kSuper0 - 1) / kSuper0) * ((n1 + s1 - 1) / s1);
+}
 __host__ __device__ inline int64_t super_grid_blocks(int64_t n0, int64_t n1) {
-    const int64_t nst = ((n0 + kSuper0 - 1) / kSuper0) * ((n1 + kSuper1 - 1) / kSuper1);
-    return (nst + kXcds - 1) / kXcds * kXcds * (kSuper0 * kSuper1);
+    const int64_t nst = super_blocks(n0, n1), per_block = kSuper0 * super_width(n1);
+    if (nst < kFewBlocks) return (nst * per_block + kXcds - 1) / kXcds * kXcds;
+    return (nst + kXcds - 1) / kXcds * kXcds * per_block;
 }
 __device__ __forceinline__ bool decode_tile(int64_t bid, int64_t n0, int64_t n1, int64_t& t0, int64_t& t1) {
-    const int64_t nst1 = (n1 + kSuper1 - 1) / kSuper1;
-    const int64_t xcd = bid % kXcds, q = bid / kXcds;
-    const int64_t st = (q / (kSuper0 * kSuper1)) * kXcds + xcd;
-    const int w = (int)(q % (kSuper0 * kSuper1));
-    t0 = (st / nst1) * kSuper0 + w / kSuper1;
-    t1 = (st % nst1) * kSuper1 + w % kSuper1;
-    return t0 < n0 && t1 < n1;
+    const int64_t s1 = super_width(n1);
+    const int64_t per_block = kSuper0 * s1;
+    const int64_t nst1 = (n1 + s1 - 1) / s1;
+    const int64_t nst = super_blocks(n0, n1);
+    const int64_t xcd = bid % kXcds, q = bid / kXcds;   // workgroup ids go round the XCDs
+    int64_t st;
+    int w;
+    if (nst < kFewBlocks) {
+        const int64_t per_xcd = (nst * per_block + kXcds - 1) / kXcds;
+        const int64_t seq = xcd * per_xcd + q;
+        st = seq / per_block;
+        w = (int)(seq % per_block);
+    } else {
+        st = (q / per_block) * kXcds + xcd;
+        w = (int)(q % per_block);
+    }
+    t0 = (st / nst1) * kSuper0 + w / s1;
+    t1 = (st % nst1) * s1 + w % s1;
+    return st < nst && t0 < n0 && t1 < n1;
 }
 
 // Accumulator element (mi, r) of a lane sits at row mi*32 + 8*(r/4) + 4*(lane/32) + r%4 of the
