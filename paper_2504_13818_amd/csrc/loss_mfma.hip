@@ -52,6 +52,8 @@ constexpr int kDist = kStages - 1;                 // k-tiles in flight ahead of
 constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
 constexpr int kQPitch = 2 * kTile + 8;             // bytes per token row of the q tile staged in LDS
 constexpr int kRecomputeLdsBytes = kTile * kQPitch > kLdsBytes ? kTile * kQPitch : kLdsBytes;   // 130 KiB
+constexpr int kHPitch = 4 * kTile + 16;            // bytes per token row of the d_hidden half-tile staged in LDS
+constexpr int kDhLdsBytes = 128 * kHPitch > kLdsBytes ? 128 * kHPitch : kLdsBytes;   // 130 KiB
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kInvLogitScale = 1.0f / (kWScale * kHScale);   // logits are accumulated as kWScale kHScale z
 constexpr int kXcds = 8;
@@ -200,10 +202,68 @@ __device__ __forceinline__ E read_frag(const unsigned char* stage, int rd, int k
 //   then     wait until this wave's share of tile kt+1 has landed, workgroup barrier;
 //   phase 1: MFMAs on F1, interleaved with the fragment reads of tile kt+1's F0.
 // The interleaving is pinned with scheduling barriers: left alone, the compiler issues the loads
-// back to back, and the matrix pipe idles while the vector-memory queue drains.  Past the last
-// tile the loads repeat the last tile into stages nobody reads again, so the loop body stays
-// branch-free.  On return each operand pointer rests on its last tile, nothing is in flight, and
-// the LDS ring may be reused after a barrier.
+// back to back, and the matrix pipe idles while the vector-memory queue drains.
+// Every load that is issued is of a tile that will be multiplied: the last kDist tiles run in a tail
+// loop that loads nothing.  (Loads issued past the end, into stages nobody reads, were once used to
+// keep one branch-free body; their data could still land in LDS after the loop's final s_waitcnt
+// vmcnt(0) and workgroup barrier, on top of whatever the kernel's epilogue had staged there.)
+// On return nothing is in flight and the LDS ring may be reused after a barrier.
+template <typename E, bool AKM, bool BKM, bool LOAD>
+__device__ __forceinline__ void k_step(Operand& A, Operand& B, const unsigned char* cur, const unsigned char* nxt,
+                                       unsigned char* dst, unsigned dsta, const LaneGeom& g, E (&fa)[2][4],
+                                       E (&fb)[2][4], f32x16 (&acc)[4][4]) {
+    constexpr bool kAsm = AKM || BKM;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
+        if constexpr (LOAD) {
+            if (i < 4) {
+                load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
+                A.ptr[i] += A.step;
+            } else {
+                load_to_lds_16<kAsm>(B.ptr[i - 4], dst + kOperandBytes + (i - 4) * 4096,
+                                     dsta + kOperandBytes + (i - 4) * 4096);
+                B.ptr[i - 4] += B.step;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
+        // all of F1 is requested in the first four slots (in the order phase 1 consumes it), so that
+        // the wait before the barrier finds it long since delivered
+        if (i == 0) { fa[1][0] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 0, 1);
+                      fb[1][0] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 0, 1); }
+        if (i == 1) { fb[1][1] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 1, 1);
+                      fb[1][2] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 2, 1); }
+        if (i == 2) { fb[1][3] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 3, 1);
+                      fa[1][1] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 1, 1); }
+        if (i == 3) { fa[1][2] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 2, 1);
+                      fa[1][3] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 3, 1); }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // loads return in order: with loads still being issued, everything but the newest kDist-1 tiles is
+    // in LDS; in the tail everything is waited for
+    if constexpr (LOAD) wait_vmcnt<8 * (kDist - 1)>();
+    else wait_vmcnt<0>();
+    wait_lgkmcnt0();                 // this wave's reads of `cur` are done before others may refill it
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
+        { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
+        if (i == 0) { fa[0][0] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 0, 0);
+                      fb[0][0] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 0, 0); }
+        if (i == 1) { fb[0][1] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 1, 0);
+                      fb[0][2] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 2, 0); }
+        if (i == 2) { fb[0][3] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 3, 0);
+                      fa[0][1] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 1, 0); }
+        if (i == 3) { fa[0][2] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 2, 0);
+                      fa[0][3] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 3, 0); }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <typename E, bool AKM = false, bool BKM = false>
 __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned char* lds,
                                        const LaneGeom& g, f32x16 (&acc)[4][4]) {
@@ -211,28 +271,28 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
     unsigned char* wave_base = lds + g.wave * 1024;
     const unsigned wave_lds = __builtin_amdgcn_readfirstlane(
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)wave_base);
-    int issued = 0;
     E fa[2][4], fb[2][4];
     __builtin_amdgcn_s_barrier();   // every wave has left the ring (previous use)
+    const int ahead = KT < kDist ? KT : kDist;   // tiles requested before the first one is multiplied
 #pragma unroll
     for (int t = 0; t < kDist; ++t) {
-        const bool more = issued + 1 < KT;
-        const int64_t adva = more ? A.step : 0, advb = more ? B.step : 0;
-        unsigned char* dst = wave_base + t * kStageBytes;
-        const unsigned dsta = wave_lds + t * kStageBytes;
+        if (t < ahead) {
+            unsigned char* dst = wave_base + t * kStageBytes;
+            const unsigned dsta = wave_lds + t * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
-            A.ptr[i] += adva;
-        }
+            for (int i = 0; i < 4; ++i) {
+                load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
+                A.ptr[i] += A.step;
+            }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            load_to_lds_16<kAsm>(B.ptr[i], dst + kOperandBytes + i * 4096, dsta + kOperandBytes + i * 4096);
-            B.ptr[i] += advb;
+            for (int i = 0; i < 4; ++i) {
+                load_to_lds_16<kAsm>(B.ptr[i], dst + kOperandBytes + i * 4096, dsta + kOperandBytes + i * 4096);
+                B.ptr[i] += B.step;
+            }
         }
-        ++issued;
     }
-    wait_vmcnt<8 * (kDist - 1)>();
+    if (KT >= kDist) wait_vmcnt<8 * (kDist - 1)>();   // the first tile is in
+    else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -240,63 +300,19 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
         fb[0][i] = read_frag<E, BKM>(lds, g.b_rd, g.b_km, g.e6, g.cx16, i, 0);
     }
     int st = 0, fill = kDist;
-    for (int kt = 0; kt < KT; ++kt) {
-        const unsigned char* cur = lds + st * kStageBytes;
+    int kt = 0;
+    for (; kt + kDist < KT; ++kt) {   // tile kt + kDist goes into the stage consumed in the previous iteration
         const int stn = (st + 1 == kStages) ? 0 : st + 1;
-        const unsigned char* nxt = lds + stn * kStageBytes;
-        unsigned char* dst = wave_base + fill * kStageBytes;
-        const unsigned dsta = wave_lds + fill * kStageBytes;
-        const bool more = issued + 1 < KT;
-        const int64_t adva = more ? A.step : 0, advb = more ? B.step : 0;
-        ++issued;
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
-            if (i < 4) {
-                load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
-                A.ptr[i] += adva;
-            } else {
-                load_to_lds_16<kAsm>(B.ptr[i - 4], dst + kOperandBytes + (i - 4) * 4096,
-                                     dsta + kOperandBytes + (i - 4) * 4096);
-                B.ptr[i - 4] += advb;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
-            // all of F1 is requested in the first four slots (in the order phase 1 consumes it), so that
-            // the wait before the barrier finds it long since delivered
-            if (i == 0) { fa[1][0] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 0, 1);
-                          fb[1][0] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 0, 1); }
-            if (i == 1) { fb[1][1] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 1, 1);
-                          fb[1][2] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 2, 1); }
-            if (i == 2) { fb[1][3] = read_frag<E, BKM>(cur, g.b_rd, g.b_km, g.e6, g.cx16, 3, 1);
-                          fa[1][1] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 1, 1); }
-            if (i == 3) { fa[1][2] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 2, 1);
-                          fa[1][3] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 3, 1); }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        wait_vmcnt<8 * (kDist - 1)>();   // loads return in order: everything but the newest kDist-1 tiles is in LDS
-        wait_lgkmcnt0();                 // this wave's reads of `cur` are done before others may refill it
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
-            { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[1][mi], fb[1][ni], acc[mi][ni]); }
-            if (i == 0) { fa[0][0] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 0, 0);
-                          fb[0][0] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 0, 0); }
-            if (i == 1) { fb[0][1] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 1, 0);
-                          fb[0][2] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 2, 0); }
-            if (i == 2) { fb[0][3] = read_frag<E, BKM>(nxt, g.b_rd, g.b_km, g.e6, g.cx16, 3, 0);
-                          fa[0][1] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 1, 0); }
-            if (i == 3) { fa[0][2] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 2, 0);
-                          fa[0][3] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 3, 0); }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        k_step<E, AKM, BKM, true>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes,
+                                  wave_base + fill * kStageBytes, wave_lds + fill * kStageBytes, g, fa, fb, acc);
         st = stn;
         fill = (fill + 1 == kStages) ? 0 : fill + 1;
     }
-    wait_vmcnt<0>();
+    for (; kt < KT; ++kt) {           // the last tiles: nothing left to request
+        const int stn = (st + 1 == kStages) ? 0 : st + 1;
+        k_step<E, AKM, BKM, false>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes, nullptr, 0u, g, fa, fb, acc);
+        st = stn;
+    }
     wait_lgkmcnt0();
 }
 
@@ -318,6 +334,8 @@ __host__ __device__ inline int64_t super_width(int64_t n1) {
     const int64_t cols = (n1 + kSuper1 - 1) / kSuper1;
     return (n1 + cols - 1) / cols;
 }
+// The caller of decode_tile passes exactly the n0, n1 the launch was sized with (super_grid_blocks): the
+// mapping of a launch with few blocks depends on both.
 // Blocks go round the XCDs (block b to XCD b mod 8), which keeps the XCDs on neighbouring blocks at any
 // time.  A launch with few blocks (d_w_lm: one or two rounds of long tiles) would leave the XCDs
 // unevenly loaded that way, so there each XCD takes one contiguous eighth of the slots (tiles, and the
@@ -374,14 +392,14 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
                                                      const uint16_t* __restrict__ ht,
                                                      const uint16_t* __restrict__ wt,
                                                      int d, int V, int vt0, int nvt_launch,
-                                                     int64_t slot_stride,
+                                                     int ntt_grid, int64_t slot_stride,
                                                      float* __restrict__ pmax, float* __restrict__ psum,
                                                      float* __restrict__ zy) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
     int64_t tt, vt;
-    if (!decode_tile(blockIdx.x, ntt, nvt_launch, tt, vt)) return;
+    if (!decode_tile(blockIdx.x, ntt_grid, nvt_launch, tt, vt) || tt >= ntt) return;
     vt += vt0;
     const LaneGeom g = lane_geom();
     const int KT = d / kBK;
@@ -476,13 +494,13 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 __global__ __launch_bounds__(256, 1) void recompute_kernel(
     const LossHeader* __restrict__ hdr, const int32_t* __restrict__ tok,
     const float* __restrict__ lse, const uint16_t* __restrict__ ht,
-    const uint16_t* __restrict__ wt, int d, int V, int v0, int vc, int64_t ldq,
+    const uint16_t* __restrict__ wt, int d, int V, int v0, int vc, int ntt_grid, int64_t ldq,
     _Float16* __restrict__ q) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
     int64_t tt, vt;
-    if (!decode_tile(blockIdx.x, ntt, vc / kTile, tt, vt)) return;
+    if (!decode_tile(blockIdx.x, ntt_grid, vc / kTile, tt, vt) || tt >= ntt) return;
     if ((int64_t)v0 + vt * kTile >= V) return;   // past the vocabulary: the gradient kernels stop there too
     const LaneGeom g = lane_geom();
     const int KT = d / kBK;
@@ -567,12 +585,12 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
                                                     const float* __restrict__ gvec,
                                                     const uint16_t* __restrict__ w16,
                                                     const uint16_t* __restrict__ q, int64_t ldq, int d,
-                                                    int V, int v0, int vc, float* __restrict__ d_hidden) {
+                                                    int V, int v0, int vc, int ntt_grid, float* __restrict__ d_hidden) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_valid = hdr->n_valid;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
     int64_t tt, kt0;
-    if (!decode_tile(blockIdx.x, ntt, (d + kTile - 1) / kTile, tt, kt0)) return;
+    if (!decode_tile(blockIdx.x, ntt_grid, (d + kTile - 1) / kTile, tt, kt0) || tt >= ntt) return;
     const LaneGeom g = lane_geom();
 
     Operand A, B;
@@ -584,24 +602,57 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     const int vwidth = min(vc, (V - v0 + kTile - 1) / kTile * kTile);   // whole tiles that hold vocabulary
     k_loop<f16x8, true, false>(A, B, vwidth / kBK, lds, g, acc);
 
+    // The tile is added to d_hidden through LDS, half of its tokens at a time: a lane holds 4 consecutive
+    // k of one token, so updating from registers would touch 32-byte pieces of 32 different rows per
+    // instruction; staged as [token][k] rows (pitch 1040 B: the 8 rows one LDS write cycle covers fall
+    // into different banks), every global load and store covers one whole 1 KiB row segment.
+    for (int half = 0; half < 2; ++half) {
+        __syncthreads();   // the ring (first pass) or the previous half has been consumed
+        if (g.wn == half) {
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        const int64_t p = tt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
-        if (p >= n_valid) continue;
-        const float scale = gvec[p] * (-1.0f / (kQScale * kWScale));
-        float* row = d_hidden + (int64_t)row_map[p] * d;
+            for (int ni = 0; ni < 4; ++ni) {
+                const int tloc = ni * 32 + (g.lane & 31);
+                const int64_t p = tt * kTile + half * 128 + tloc;
+                const float scale = (p < n_valid) ? gvec[p] * (-1.0f / (kQScale * kWScale)) : 0.0f;
+                unsigned char* row = lds + tloc * kHPitch + (g.wm * 128 + 4 * (g.lane >> 5)) * 4;
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+                for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int k = (int)kt0 * kTile + g.wm * 128 + mi * 32 + 8 * b + 4 * (g.lane >> 5);
-                if (k >= d) continue;
-                f32x4 v;
+                    for (int b = 0; b < 4; ++b) {
+                        f32x4 v;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v[c] = acc[mi][ni][b * 4 + c] * scale;
-                f32x4* dst = reinterpret_cast<f32x4*>(row + k);
-                *dst = v + *dst;
+                        for (int c = 0; c < 4; ++c) v[c] = acc[mi][ni][b * 4 + c] * scale;
+                        *reinterpret_cast<f32x4*>(row + (mi * 32 + 8 * b) * 4) = v;
+                    }
             }
+        }
+        __syncthreads();
+        // wave w updates rows 32 w .. 32 w + 31 of this half, eight rows in flight at a time
+        const int64_t p0 = tt * kTile + half * 128 + g.wave * 32;
+        const int live = (int)(n_valid - p0 < 32 ? (n_valid - p0 < 0 ? 0 : n_valid - p0) : 32);   // rows are in token order
+        const int my_row = (g.lane < live) ? row_map[p0 + g.lane] : 0;
+        const int k = (int)kt0 * kTile + g.lane * 4;
+        if (k < d) {
+            for (int i0 = 0; i0 < live; i0 += 8) {
+                f32x4* dst[8];
+                f32x4 cur[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int src_lane = i0 + j < live ? i0 + j : i0;   // past the end: a row already in flight
+                    const int64_t row = __builtin_amdgcn_readlane(my_row, src_lane);
+                    dst[j] = reinterpret_cast<f32x4*>(d_hidden + row * d + k);
+                    cur[j] = *dst[j];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (i0 + j < live) {
+                        const int r = g.wave * 32 + i0 + j;
+                        const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * kHPitch + g.lane * 16);
+                        *dst[j] = v + cur[j];
+                    }
+                }
+            }
+        }
     }
 }
 
@@ -843,7 +894,7 @@ pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
         PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nl)), dim3(256),
                     kLdsBytes, a.stream, hdr, reinterpret_cast<const int32_t*>(ws + p.off_tok),
                     reinterpret_cast<const uint16_t*>(ht), reinterpret_cast<const uint16_t*>(wt), a.d, a.V, (int)vt0,
-                    (int)nl, p.ncap_ld, reinterpret_cast<float*>(ws + p.off_pmax),
+                    (int)nl, (int)ntt, p.ncap_ld, reinterpret_cast<float*>(ws + p.off_pmax),
                     reinterpret_cast<float*>(ws + p.off_psum), reinterpret_cast<float*>(ws + p.off_zy));
         if ((st = check_launch("token loss forward")) != PODS_OK) return st;
     }
@@ -867,7 +918,7 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
     const auto* w = static_cast<const uint16_t*>(a.w_lm);
     pods_status st;
     if ((st = reserve(reinterpret_cast<const void*>(recompute_kernel), "token loss recompute", kRecomputeLdsBytes)) != PODS_OK) return st;
-    if ((st = reserve(reinterpret_cast<const void*>(dh_kernel), "token loss d_hidden")) != PODS_OK) return st;
+    if ((st = reserve(reinterpret_cast<const void*>(dh_kernel), "token loss d_hidden", kDhLdsBytes)) != PODS_OK) return st;
     if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
 
     const int64_t per_row = a.d / 8;
@@ -889,11 +940,11 @@ pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
         const int v0 = c * p.vc;
         if (v0 >= a.V) break;
         PODS_LAUNCH("token loss recompute", a.stream, recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
-                           kRecomputeLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, p.ldq, dz);
+                           kRecomputeLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, (int)ntt, p.ldq, dz);
         if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
-        PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kLdsBytes,
+        PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kDhLdsBytes,
                            a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
-                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, a.d_hidden);
+                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, (int)ntt, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
                            kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(h16),
