@@ -59,6 +59,21 @@ def test_bf16_no_lengths_and_determinism(pods):
     assert a["loss"] == b["loss"]
 
 
+@pytest.mark.parametrize("R,T,d,V", [(4, 320, 2048, 151936), (3, 700, 512, 20000), (9, 130, 768, 9000)])
+def test_bf16_padded_batches_are_bitwise_repeatable(pods, R, T, d, V):
+    """Ragged batches whose padded capacity spans more 256-token tiles than their valid tokens do, small
+    enough that a launch has only a few blocks of tiles: every tile must be taken by exactly one
+    workgroup (two would race on d_hidden), so four runs agree bit for bit and with the oracle."""
+    case = H.loss_case(1, R, T, d, V, sigma=0.05)
+    assert (int(case["lengths"].sum()) + 255) // 256 < (R * T + 255) // 256
+    scale = float(R * case["lengths"].mean())
+    runs = [H.gpu_loss(pods, torch, case, grad_scale=scale) for _ in range(4)]
+    for other in runs[1:]:
+        for key in ("logp", "d_hidden", "d_w"):
+            assert np.array_equal(runs[0][key], other[key]), key
+    H.check_loss(runs[0], H.oracle_loss(case, grad_scale=scale))
+
+
 @pytest.mark.parametrize("cfg,R,T", [(1, 4, 320), (2, 2, 400), (4, 6, 160)])
 def test_bf16_full_head_reduced_tokens(pods, cfg, R, T):
     """Full d and V of the config (lm_head shape), a few hundred valid tokens."""
