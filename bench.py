@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 / fp16 MFMA peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
 KERNEL_SYMBOLS = {"token loss forward": "fwd_kernel", "token loss recompute": "recompute_kernel",
                   "token loss d_hidden": "dh_kernel", "token loss d_w_lm": "dw_kernel",
                   "pods_select": "select_kernel"}
@@ -85,7 +85,7 @@ def summarize_traffic(fetch_csv, write_csv, out_path=TRAFFIC_FILE):
 
 
 def recorded_traffic(kernel):
-    """HBM bytes per launch (fetch + write) from profiles/traffic.json, or None when absent or stale."""
+    """HBM bytes per launch (fetch + write) from profiles/hbm_traffic_counters.txt, or None when absent or stale."""
     try:
         t = json.load(open(TRAFFIC_FILE))
     except (OSError, ValueError):
@@ -213,7 +213,7 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run a 1 GiB copy kernel, the calibration for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--summarize-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
-                    help="no GPU work: write profiles/traffic.json from two --pmc counter_collection.csv files")
+                    help="no GPU work: write profiles/hbm_traffic_counters.txt from two --pmc counter_collection.csv files")
     args = ap.parse_args()
     if args.summarize_traffic:
         print(json.dumps(summarize_traffic(*args.summarize_traffic), indent=1))

@@ -143,3 +143,20 @@ def test_c_oracle_rejects_bad_arguments():
     r = np.zeros((2, 4), dtype=np.float32)
     with pytest.raises(ValueError):
         fast.select(r, 5)
+
+
+def test_theorem2_cases_from_the_golden_file():
+    """tests/golden/theorem2_binary_cases.txt: the paper's closed form for binary rewards (Theorem 2),
+    worked by hand; every oracle variant must keep exactly that many ones, wherever the ones sit."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "theorem2_binary_cases.txt")
+    rng = np.random.default_rng(42)
+    rows = [tuple(int(x) for x in line.split()) for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) >= 25
+    for n, m, c1, want in rows:
+        r = np.zeros(n, dtype=np.float32)
+        r[rng.choice(n, c1, replace=False)] = 1.0
+        for sel, _k in (po.select_exact(r, m), po.select_prefix(r, m)):
+            assert len(set(sel)) == m and int(sum(r[i] for i in sel)) == want, (n, m, c1)
+        idx, _, _ = fast.select(r[None], m)
+        assert int(r[idx[0]].sum()) == want, (n, m, c1)
