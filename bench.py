@@ -37,13 +37,16 @@ def sources_of(kernel):
 
 
 def source_digest(names=LOSS_SOURCES):
-    """sha256 over a kernel family's HIP sources: HBM-traffic counters are only quoted for the
-    kernels they were taken on."""
+    """sha256 over a kernel family's HIP sources (comments and whitespace aside): HBM-traffic counters
+    are only quoted for the kernels they were taken on."""
     import hashlib
+    import re
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2504_13818_amd", "csrc")
     for name in names:
-        h.update(open(os.path.join(csrc, name), "rb").read())
+        text = open(os.path.join(csrc, name), encoding="utf-8").read()
+        text = re.sub(r"//[^\n]*", "", text)                      # comments and layout do not change a kernel
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()
 
 
