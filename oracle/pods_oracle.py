@@ -231,13 +231,18 @@ def advantage_before(rewards: np.ndarray, sel_idx: np.ndarray, std_eps: float = 
 
 def token_rows(h: np.ndarray, w: np.ndarray, y: np.ndarray, old_logp: np.ndarray,
                a: np.ndarray, c: np.ndarray, clip_eps: float, grad_scale: float = 1.0,
-               gemm_dtype=np.float64):
+               gemm_dtype=np.float64, ref_logp: np.ndarray | None = None, kl_coef: float = 0.0):
     """The objective's inner term for K independent token positions.
 
     h[K, d] hidden rows, w[V, d], y[K] generated token, old_logp[K] = log pi_fixed(y),
     a[K] the rollout's advantage, c[K] = 1 / (R * |o_i|) the averaging weight.
-    Returns dict with logp[K], obj[K] (the min[...] term), g[K] = d loss / d logp,
-    dz[K, V] = d loss / d logits, d_h[K, d]; all float64.
+    Returns dict with logp[K], obj[K] (the min[...] term, minus the KL penalty if any),
+    g[K] = d loss / d logp, dz[K, V] = d loss / d logits, d_h[K, d]; all float64.
+
+    KL penalty (Table 2 lists a KL coefficient, 0.04 in one setting and 0 in the others; the paper
+    gives no formula).  Reading taken: the per-token estimator of the GRPO objective the paper
+    builds on, with x = log pi_ref(y) - log pi_theta(y):  KL = exp(x) - x - 1  (>= 0, 0 iff the two
+    agree), subtracted from the token's term with weight kl_coef.
     """
     K = h.shape[0]
     wg = w.astype(gemm_dtype, copy=False)
@@ -254,6 +259,10 @@ def token_rows(h: np.ndarray, w: np.ndarray, y: np.ndarray, old_logp: np.ndarray
     # d obj / d rho: a where the unclipped term is the one selected, else 0.
     inactive = ((a > 0) & (rho > 1.0 + clip_eps)) | ((a < 0) & (rho < 1.0 - clip_eps))
     dobj_dlogp = np.where(inactive, 0.0, a * rho)
+    if ref_logp is not None and kl_coef != 0.0:
+        x = ref_logp.astype(np.float64) - logp
+        obj = obj - kl_coef * (np.exp(x) - x - 1.0)
+        dobj_dlogp = dobj_dlogp - kl_coef * (1.0 - np.exp(x))                  # d(-KL)/d logp = exp(x) - 1
     g = -c.astype(np.float64) * dobj_dlogp * grad_scale                        # loss = -objective
     p = np.exp(z - lse[:, None])                                               # softmax
     dz = -g[:, None] * p
@@ -265,9 +274,9 @@ def token_rows(h: np.ndarray, w: np.ndarray, y: np.ndarray, old_logp: np.ndarray
 def grpo_token_loss(hidden: np.ndarray, w: np.ndarray, tokens: np.ndarray, old_logp: np.ndarray,
                     adv: np.ndarray, lengths: np.ndarray | None, clip_eps: float,
                     grad_scale: float = 1.0, gemm_dtype=np.float64, block: int = 256,
-                    want_dw: bool = True):
-    """loss = -(1/R) sum_i (1/|o_i|) sum_{t<|o_i|} min[rho a_i, clip(rho, 1-eps, 1+eps) a_i]
-    over R kept rollouts, and its gradient.
+                    want_dw: bool = True, ref_logp: np.ndarray | None = None, kl_coef: float = 0.0):
+    """loss = -(1/R) sum_i (1/|o_i|) sum_{t<|o_i|} { min[rho a_i, clip(rho, 1-eps, 1+eps) a_i]
+    - kl_coef KL_t } over R kept rollouts, and its gradient (KL_t: see token_rows; absent by default).
 
     hidden[R, T, d], w[V, d], tokens[R, T], old_logp[R, T], adv[R], lengths[R] (None: all T).
     Returns dict(loss, logp[R, T], d_hidden[R, T, d], d_w[V, d]); float64.  Positions at or past
@@ -292,7 +301,7 @@ def grpo_token_loss(hidden: np.ndarray, w: np.ndarray, tokens: np.ndarray, old_l
         hb = hidden[bi, bt]
         cb = 1.0 / (R * lens[bi].astype(np.float64))
         out = token_rows(hb, w, tokens[bi, bt], old_logp[bi, bt], adv[bi], cb, clip_eps,
-                         grad_scale, gemm_dtype)
+                         grad_scale, gemm_dtype, None if ref_logp is None else ref_logp[bi, bt], kl_coef)
         loss -= float((cb * out["obj"]).sum())
         logp[bi, bt] = out["logp"]
         d_hidden[bi, bt] = out["d_h"]

@@ -154,3 +154,70 @@ def test_fp32_gemm_variant_close_to_fp64():
                            gemm_dtype=np.float32, block=5)
     assert a["loss"] == pytest.approx(b["loss"], rel=1e-5)
     assert np.allclose(a["d_w"], b["d_w"], rtol=1e-4, atol=1e-6)
+
+
+# ---- KL penalty (Table 2 lists a coefficient; the estimator is a reading, see the oracle) ----------
+
+def _ref_logp(seed, old):
+    return (old + np.random.default_rng(seed + 100).normal(0, 0.3, old.shape)).astype(np.float32)
+
+
+def test_kl_definition_by_plain_loops_and_sign():
+    h, w, y, old, adv, lens = _problem(5)
+    ref = _ref_logp(5, old)
+    R = h.shape[0]; eps = 0.2; beta = 0.04
+    total, kl_total = 0.0, 0.0
+    for i in range(R):
+        acc = 0.0
+        for t in range(lens[i]):
+            lp = log_softmax(w @ h[i, t])[y[i, t]]
+            rho = math.exp(lp - old[i, t])
+            x = float(ref[i, t]) - lp
+            kl = math.exp(x) - x - 1.0
+            assert kl >= 0.0
+            kl_total += kl
+            acc += min(rho * adv[i], min(max(rho, 1 - eps), 1 + eps) * adv[i]) - beta * kl
+        total += acc / lens[i]
+    with_kl = po.grpo_token_loss(h, w, y, old, adv, lens, eps, ref_logp=ref, kl_coef=beta)["loss"]
+    without = po.grpo_token_loss(h, w, y, old, adv, lens, eps)["loss"]
+    assert with_kl == pytest.approx(-total / R, rel=1e-12)
+    assert kl_total > 0 and with_kl > without                      # a penalty raises the loss
+
+
+def test_kl_vanishes_at_the_reference_and_with_zero_coefficient():
+    h, w, y, old, adv, lens = _problem(6)
+    base = po.grpo_token_loss(h, w, y, old, adv, lens, 0.2)
+    same = po.grpo_token_loss(h, w, y, old, adv, lens, 0.2, ref_logp=_ref_logp(6, old), kl_coef=0.0)
+    for k in ("logp", "d_hidden", "d_w"):
+        assert np.array_equal(base[k], same[k])
+    # ref = the policy's own log-probs: KL and its gradient are zero (its minimum)
+    at_ref = po.grpo_token_loss(h, w, y, old, adv, lens, 0.2, ref_logp=base["logp"].astype(np.float64), kl_coef=5.0)
+    assert at_ref["loss"] == pytest.approx(base["loss"], rel=1e-12)
+    assert np.allclose(at_ref["d_hidden"], base["d_hidden"], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", [7, 8])
+def test_kl_finite_differences(seed):
+    h, w, y, old, adv, lens = _problem(seed, sigma=0.3)
+    ref = _ref_logp(seed, old)
+    eps, beta = 0.2, 0.7
+    out = po.grpo_token_loss(h, w, y, old, adv, lens, eps, grad_scale=3.0, ref_logp=ref, kl_coef=beta)
+    f = lambda hh, ww: po.grpo_token_loss(hh, ww, y, old, adv, lens, eps, want_dw=False, ref_logp=ref, kl_coef=beta)["loss"]
+    step = 1e-6
+    g = np.random.default_rng(seed)
+    for _ in range(20):
+        i, t, k = g.integers(0, h.shape[0]), g.integers(0, h.shape[1]), g.integers(0, h.shape[2])
+        hp, hm = h.copy(), h.copy(); hp[i, t, k] += step; hm[i, t, k] -= step
+        fd = 3.0 * (f(hp, w) - f(hm, w)) / (2 * step)
+        assert out["d_hidden"][i, t, k] == pytest.approx(fd, rel=2e-6, abs=1e-8)
+        v, k = g.integers(0, w.shape[0]), g.integers(0, w.shape[1])
+        wp, wm = w.copy(), w.copy(); wp[v, k] += step; wm[v, k] -= step
+        fd = 3.0 * (f(h, wp) - f(h, wm)) / (2 * step)
+        assert out["d_w"][v, k] == pytest.approx(fd, rel=2e-6, abs=1e-8)
+
+
+def test_kl_second_order_expansion():
+    """Near the reference the estimator is x^2 / 2 to leading order (the KL of nearby distributions)."""
+    for x in (1e-3, -2e-3, 5e-3):
+        kl = math.exp(x) - x - 1.0
+        assert kl == pytest.approx(x * x / 2, rel=abs(x))
