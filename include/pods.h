@@ -193,6 +193,23 @@ pods_status grpo_token_loss_fwd_bwd_accumulate(const void* hidden, const void* w
                                                float* d_w_lm, void* workspace, size_t workspace_bytes,
                                                void* stream);
 
+/* The same with a KL penalty towards a reference policy.  Table 2 lists a KL coefficient (0.04 in one
+ * setting, 0 in the others) but the paper gives no formula; taken here is the per-token estimator of the
+ * GRPO objective the paper builds on: with x = ref_logp - log pi_theta(y), KL = exp(x) - x - 1 (>= 0),
+ * and the token's term becomes min[...] - kl_coef * KL.
+ *
+ *   ref_logp        [R, T] float32, in: log pi_ref of the generated token (a constant)
+ *   kl_coef         >= 0
+ *   accumulate_d_w  non-zero: d_w_lm += gradient, as in grpo_token_loss_fwd_bwd_accumulate
+ * Everything else as in grpo_token_loss_fwd_bwd. */
+pods_status grpo_token_loss_fwd_bwd_kl(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                       const float* old_logp, const float* ref_logp, const float* adv,
+                                       const int32_t* lengths, int32_t R, int32_t T, int32_t d, int32_t V,
+                                       pods_dtype dt, float clip_eps, float kl_coef, float grad_scale,
+                                       int32_t accumulate_d_w, float* loss, float* logp_out,
+                                       float* d_hidden, float* d_w_lm, void* workspace,
+                                       size_t workspace_bytes, void* stream);
+
 /* Per-launch timing for benchmarks (not part of the method).  pods_profile_enable(1) makes every
  * later library call on this thread bracket each of its kernel launches with a pair of HIP events
  * on the call's stream, and discards earlier records; pods_profile_enable(0) stops recording.

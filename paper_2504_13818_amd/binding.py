@@ -11,7 +11,7 @@ _lib = None
 PODS_F32, PODS_BF16 = 0, 1
 PODS_RULE_MAXVAR, PODS_RULE_MAXR, PODS_RULE_PERC, PODS_RULE_RAND = 0, 1, 2, 3
 EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_advantage_before",
-                    "pods_gather_rows", "grpo_token_loss_fwd_bwd_accumulate",
+                    "pods_gather_rows", "grpo_token_loss_fwd_bwd_accumulate", "grpo_token_loss_fwd_bwd_kl",
                     "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
@@ -57,6 +57,10 @@ def load():
         f.restype = ctypes.c_int
         f.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                       ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.grpo_token_loss_fwd_bwd_kl.restype = ctypes.c_int
+    lib.grpo_token_loss_fwd_bwd_kl.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
+                                               ctypes.c_int, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp, _vp, _sz,
+                                               _vp]
     lib.pods_gather_rows.restype = ctypes.c_int
     lib.pods_gather_rows.argtypes = [_vp, _vp, _i32, _i32, _i32, _sz, _vp, _vp]
     lib.pods_profile_enable.restype = ctypes.c_int
@@ -205,12 +209,14 @@ def pods_gather_rows(per_rollout, sel_idx, out=None, stream=None):
 
 def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_eps: float,
                             grad_scale: float = 1.0, workspace=None, want_logp: bool = True,
-                            out=None, stream=None, accumulate_d_w: bool = False):
+                            out=None, stream=None, accumulate_d_w: bool = False, ref_logp=None,
+                            kl_coef: float = 0.0):
     """Returns dict(loss[1], logp[R, T] or None, d_hidden[R, T, d], d_w_lm[V, d]), float32 on device.
 
     `workspace` is a uint8 CUDA tensor (allocated at the recommended size when None); `out` may
     carry preallocated loss / logp / d_hidden / d_w_lm tensors.  With accumulate_d_w the gradient is
-    added to out["d_w_lm"] (grpo_token_loss_fwd_bwd_accumulate).
+    added to out["d_w_lm"] (grpo_token_loss_fwd_bwd_accumulate).  With ref_logp[R, T] float32 the KL
+    penalty kl_coef * KL is subtracted from every token's term (grpo_token_loss_fwd_bwd_kl).
     """
     import torch
     dt = _dt(hidden)
@@ -238,6 +244,15 @@ def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_e
     if workspace is None:
         workspace = torch.empty((grpo_token_loss_workspace_bytes(R, T, d, V, dt),), dtype=torch.uint8,
                                 device=dev)
+    if ref_logp is not None:
+        _need(ref_logp, torch.float32, "ref_logp")
+        _check(load().grpo_token_loss_fwd_bwd_kl(
+            _ptr(hidden), _ptr(w_lm), _ptr(tokens), _ptr(old_logp), _ptr(ref_logp), _ptr(adv), _ptr(lengths), R, T,
+            d, V, dt, float(clip_eps), float(kl_coef), float(grad_scale), 1 if accumulate_d_w else 0,
+            _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["d_hidden"]), _ptr(out["d_w_lm"]), _ptr(workspace),
+            workspace.numel(), _stream(stream)))
+        out["workspace"] = workspace
+        return out
     entry = load().grpo_token_loss_fwd_bwd_accumulate if accumulate_d_w else load().grpo_token_loss_fwd_bwd
     _check(entry(
         _ptr(hidden), _ptr(w_lm), _ptr(tokens), _ptr(old_logp), _ptr(adv), _ptr(lengths), R, T, d, V,

@@ -141,7 +141,8 @@ size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int3
 }
 
 static pods_status token_loss_entry(const void* hidden, const void* w_lm, const int32_t* tokens,
-                                    const float* old_logp, const float* adv, const int32_t* lengths,
+                                    const float* old_logp, const float* ref_logp, float kl_coef,
+                                    const float* adv, const int32_t* lengths,
                                     int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
                                     float clip_eps, float grad_scale, float* loss, float* logp_out,
                                     float* d_hidden, float* d_w_lm, bool accumulate_d_w, void* workspace,
@@ -168,6 +169,7 @@ static pods_status token_loss_entry(const void* hidden, const void* w_lm, const 
                     workspace_bytes, need);
     LossArgs a;
     a.hidden = hidden; a.w_lm = w_lm; a.tokens = tokens; a.old_logp = old_logp; a.adv = adv;
+    a.ref_logp = (ref_logp != nullptr && kl_coef != 0.0f) ? ref_logp : nullptr; a.kl_coef = kl_coef;
     a.lengths = lengths; a.R = R; a.T = T; a.d = d; a.V = V; a.dt = dt; a.clip_eps = clip_eps;
     a.grad_scale = grad_scale; a.loss = loss; a.logp_out = logp_out; a.d_hidden = d_hidden;
     a.d_w_lm = d_w_lm; a.accumulate_d_w = accumulate_d_w; a.workspace = static_cast<unsigned char*>(workspace);
@@ -181,8 +183,8 @@ pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const 
                                     float clip_eps, float grad_scale, float* loss, float* logp_out,
                                     float* d_hidden, float* d_w_lm, void* workspace,
                                     size_t workspace_bytes, void* stream) {
-    return token_loss_entry(hidden, w_lm, tokens, old_logp, adv, lengths, R, T, d, V, dt, clip_eps, grad_scale,
-                            loss, logp_out, d_hidden, d_w_lm, false, workspace, workspace_bytes, stream);
+    return token_loss_entry(hidden, w_lm, tokens, old_logp, nullptr, 0.0f, adv, lengths, R, T, d, V, dt, clip_eps,
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm, false, workspace, workspace_bytes, stream);
 }
 
 pods_status grpo_token_loss_fwd_bwd_accumulate(const void* hidden, const void* w_lm, const int32_t* tokens,
@@ -192,8 +194,22 @@ pods_status grpo_token_loss_fwd_bwd_accumulate(const void* hidden, const void* w
                                                float* loss, float* logp_out, float* d_hidden,
                                                float* d_w_lm, void* workspace, size_t workspace_bytes,
                                                void* stream) {
-    return token_loss_entry(hidden, w_lm, tokens, old_logp, adv, lengths, R, T, d, V, dt, clip_eps, grad_scale,
-                            loss, logp_out, d_hidden, d_w_lm, true, workspace, workspace_bytes, stream);
+    return token_loss_entry(hidden, w_lm, tokens, old_logp, nullptr, 0.0f, adv, lengths, R, T, d, V, dt, clip_eps,
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm, true, workspace, workspace_bytes, stream);
+}
+
+pods_status grpo_token_loss_fwd_bwd_kl(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                       const float* old_logp, const float* ref_logp, const float* adv,
+                                       const int32_t* lengths, int32_t R, int32_t T, int32_t d, int32_t V,
+                                       pods_dtype dt, float clip_eps, float kl_coef, float grad_scale,
+                                       int32_t accumulate_d_w, float* loss, float* logp_out,
+                                       float* d_hidden, float* d_w_lm, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+    if (ref_logp == nullptr) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_kl: ref_logp is null");
+    if (!(kl_coef >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_kl: kl_coef < 0");
+    return token_loss_entry(hidden, w_lm, tokens, old_logp, ref_logp, kl_coef, adv, lengths, R, T, d, V, dt, clip_eps,
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm, accumulate_d_w != 0, workspace,
+                            workspace_bytes, stream);
 }
 
 pods_status pods_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,

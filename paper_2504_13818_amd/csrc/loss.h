@@ -16,6 +16,8 @@ struct LossArgs {
     const void* w_lm;
     const int32_t* tokens;
     const float* old_logp;
+    const float* ref_logp;   // log pi_ref(y) for the KL penalty, or null
+    float kl_coef;
     const float* adv;
     const int32_t* lengths;
     int32_t R, T, d, V;

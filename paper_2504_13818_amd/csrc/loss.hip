@@ -168,11 +168,13 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
 
 // Per valid token: combine the forward partials into log-sum-exp, then the surrogate of
 // Sec. 3.2: rho = exp(logp - old_logp), min[rho a, clip(rho, 1-eps, 1+eps) a], its weight
-// 1/(R len_i), and g = d loss / d logp.  Block partial sums of the loss in double.
+// 1/(R len_i), and g = d loss / d logp; with a reference policy, minus kl_coef times the per-token
+// KL estimator (Table 2 lists the coefficient).  Block partial sums of the loss in double.
 __global__ __launch_bounds__(256) void surrogate_kernel(
     LossHeader* __restrict__ hdr, const int32_t* __restrict__ row_map,
     const float* __restrict__ pmax, const float* __restrict__ psum, int slots, int64_t slot_stride,
-    const float* __restrict__ zy, const float* __restrict__ old_logp, const float* __restrict__ adv,
+    const float* __restrict__ zy, const float* __restrict__ old_logp, const float* __restrict__ ref_logp,
+    float kl_coef, const float* __restrict__ adv,
     const int32_t* __restrict__ lengths, int R, int T, float clip_eps, float grad_scale,
     float* __restrict__ lse_out, float* __restrict__ g_out, float* __restrict__ coef_out,
     float* __restrict__ logp_out, double* __restrict__ loss_part) {
@@ -199,9 +201,17 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
         const float logp = zy[p] - lse;
         const float rho = expf(logp - old_logp[flat]);
         const float lo = 1.0f - clip_eps, hi = 1.0f + clip_eps;
-        const float obj = fminf(rho * a, fminf(fmaxf(rho, lo), hi) * a);
+        float obj = fminf(rho * a, fminf(fmaxf(rho, lo), hi) * a);
         const bool inactive = (a > 0.0f && rho > hi) || (a < 0.0f && rho < lo);
-        const float gp = inactive ? 0.0f : -c * a * rho * grad_scale;
+        float dobj = inactive ? 0.0f : a * rho;   // d obj / d logp
+        if (ref_logp != nullptr) {
+            // KL penalty, per token: exp(x) - x - 1 with x = log pi_ref(y) - log pi_theta(y)
+            const float x = ref_logp[flat] - logp;
+            const float em1 = expm1f(x);
+            obj -= kl_coef * (em1 - x);
+            dobj += kl_coef * em1;
+        }
+        const float gp = -c * dobj * grad_scale;
         lse_out[p] = lse;
         g_out[p] = gp;
         coef_out[p] = gp * -expm1f(logp);  // d loss / d z_y = g (1 - softmax_y)
@@ -271,7 +281,7 @@ pods_status run_loss(const LossArgs& a) {
     if (st != PODS_OK) return st;
 
     PODS_LAUNCH("surrogate", a.stream, surrogate_kernel, dim3((unsigned)p.loss_blocks), dim3(256), 0, a.stream, hdr,
-                       row_map, pmax, psum, p.slots, p.ncap_ld, zy, a.old_logp, a.adv, a.lengths, a.R,
+                       row_map, pmax, psum, p.slots, p.ncap_ld, zy, a.old_logp, a.ref_logp, a.kl_coef, a.adv, a.lengths, a.R,
                        a.T, a.clip_eps, a.grad_scale, lse, g, coef, a.logp_out, loss_part);
     if ((st = check_launch("surrogate")) != PODS_OK) return st;
     PODS_LAUNCH("finalize_loss", a.stream, finalize_loss_kernel, dim3(1), dim3(1024), 0, a.stream, loss_part,
