@@ -50,8 +50,7 @@ __device__ __forceinline__ float g_range_scale(const LossHeader* hdr) {
 
 // Fixed power-of-two scales of the fp16 operands of the two gradient contractions.
 constexpr float kQScale = 16384.0f;  // q = kQScale softmax (0 at v = y): 0 <= q <= 2^14
-constexpr float kWScale = 256.0f;    // fp16 weight copies hold kWScale * W
-constexpr float kHScale = 0.0625f;   // fp16 transposed hidden copy holds kHScale * h
+constexpr float kWScale = 256.0f;    // the fp16 weight copy of the gradient contractions holds kWScale * W
 
 constexpr int kTile = 256;          // token / vocab / hidden tile edge of the matrix-core kernels
 constexpr int kDefaultVocabChunk = 8192;
