@@ -327,8 +327,8 @@ def main():
         "config": {"workload": f"configs[{cfg}] {c['name']}: B={B} n={n} m={m} R={R} T={T} "
                                f"valid_tokens={n_valid} d={d} V={V} {c['dtype']} eps={c['clip_eps']}",
                    "step": "pods_select + pods_advantage + grpo_token_loss_fwd_bwd",
-                   "arithmetic": "bf16 inputs multiplied as exact fp16 copies (v_mfma_f32_32x32x16_f16), fp32 accumulation; "
-                                 "fp64 selector scores"},
+                   "arithmetic": "logits: bf16 MFMA (v_mfma_f32_32x32x16_bf16); gradients: fp16 MFMA on exact fp16 copies of "
+                                 "the bf16 inputs and an fp16 softmax operand; fp32 accumulation; fp64 selector scores"},
         "roofline": roofline,
         "kernels": kernels,
         "selector": selector,
