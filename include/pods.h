@@ -9,6 +9,8 @@
  *   pods_downsample           the same selection step under any of the paper's rules: max-variance,
  *                             max-reward, percentile, random (Sec. 3.2)
  *   pods_gather_rows          the kept rollouts' records, concatenated over prompts (Sec. 3.2)
+ *   pods_downsample_gather    down-sampling, advantages and the records' copy in one launch
+ *                             (Algorithm 1, steps 3-4)
  *   pods_advantage            group-normalised advantages over the kept rollouts (Sec. 3.2)
  *   pods_advantage_before     the "Before" variant: statistics from all n rollouts of the group
  *                             (App. "On Advantage Normalization")
@@ -134,6 +136,34 @@ pods_status pods_advantage_before(const float* rewards, const int32_t* sel_idx, 
  */
 pods_status pods_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,
                              size_t row_bytes, void* dst, void* stream);
+
+/* Steps 3 and 4 of Algorithm 1 in one launch: pods_downsample, then pods_advantage (or
+ * pods_advantage_before), then pods_gather_rows for each of up to PODS_MAX_RECORDS record arrays,
+ * with the results of each step exactly as those calls define them.  One workgroup serves one
+ * prompt group, so this is the call for a training step's handful of prompts with long records;
+ * for very many small groups without records the separate pods_downsample is the faster selector.
+ *
+ *   rewards         [B, n] float32, in (needed by every rule: the advantages read it)
+ *   rand_keys       [B, n] uint32, in (PODS_RULE_RAND only; NULL otherwise)
+ *   stats_from_all  0: statistics of the m kept rewards; non-zero: of all n ("Before")
+ *   records         HOST array of num_records descriptors; each src is [B, n, row_bytes] bytes on
+ *                   the device, each dst [B*m, row_bytes] bytes on the device, not overlapping any
+ *                   src; the array is read during the call and need not outlive it
+ *   num_records     0 .. PODS_MAX_RECORDS
+ *   sel_idx         [B, m] int32, out;  sel_k [B] int32, out, may be NULL;  adv [B, m] float32, out
+ *   1 <= m <= n <= 1024 (PODS_ERR_UNSUPPORTED above that: use the separate calls).
+ */
+enum { PODS_MAX_RECORDS = 8 };
+typedef struct {
+    const void* src;
+    void* dst;
+    size_t row_bytes;
+} pods_record;
+
+pods_status pods_downsample_gather(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n,
+                                   int32_t m, pods_rule rule, float std_eps, int32_t stats_from_all,
+                                   const pods_record* records, int32_t num_records, int32_t* sel_idx,
+                                   int32_t* sel_k, float* adv, void* stream);
 
 /* Bytes of workspace grpo_token_loss_fwd_bwd wants for these sizes (a recommendation: any
  * workspace of at least grpo_token_loss_workspace_min_bytes works; below the recommendation the

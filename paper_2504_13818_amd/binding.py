@@ -11,12 +11,17 @@ _lib = None
 PODS_F32, PODS_BF16 = 0, 1
 PODS_RULE_MAXVAR, PODS_RULE_MAXR, PODS_RULE_PERC, PODS_RULE_RAND = 0, 1, 2, 3
 EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_advantage_before",
-                    "pods_gather_rows", "grpo_token_loss_fwd_bwd_accumulate", "grpo_token_loss_fwd_bwd_kl",
+                    "pods_gather_rows", "pods_downsample_gather", "grpo_token_loss_fwd_bwd_accumulate", "grpo_token_loss_fwd_bwd_kl",
                     "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
 
 _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+
+
+class PodsRecord(ctypes.Structure):
+    """pods_record of include/pods.h."""
+    _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("row_bytes", ctypes.c_size_t)]
 
 
 class PodsError(RuntimeError):
@@ -63,6 +68,9 @@ def load():
                                                _vp]
     lib.pods_gather_rows.restype = ctypes.c_int
     lib.pods_gather_rows.argtypes = [_vp, _vp, _i32, _i32, _i32, _sz, _vp, _vp]
+    lib.pods_downsample_gather.restype = ctypes.c_int
+    lib.pods_downsample_gather.argtypes = [_vp, _vp, _i32, _i32, _i32, ctypes.c_int, _f32, _i32,
+                                           ctypes.POINTER(PodsRecord), _i32, _vp, _vp, _vp, _vp]
     lib.pods_profile_enable.restype = ctypes.c_int
     lib.pods_profile_enable.argtypes = [_i32]
     lib.pods_profile_count.restype = _i32
@@ -205,6 +213,43 @@ def pods_gather_rows(per_rollout, sel_idx, out=None, stream=None):
     _check(load().pods_gather_rows(_ptr(per_rollout), _ptr(sel_idx), B, n, m, row_bytes, _ptr(out),
                                    _stream(stream)))
     return out
+
+
+def pods_downsample_gather(rewards, m: int, records=(), rule: int = PODS_RULE_MAXVAR, rand_keys=None,
+                           std_eps: float = 0.0, stats_from_all: bool = False, outs=None, stream=None):
+    """One launch for down-sampling, advantages and the kept rollouts' records.  rewards[B, n] float32;
+    records: contiguous CUDA tensors [B, n, ...] of any dtype; outs: optional preallocated [B*m, ...]
+    tensors, one per record.  Returns (sel_idx[B, m], sel_k[B], adv[B, m], [gathered records])."""
+    import torch
+    _need(rewards, torch.float32, "rewards")
+    if rand_keys is not None and not (isinstance(rand_keys, torch.Tensor) and rand_keys.is_cuda and
+                                      rand_keys.is_contiguous() and
+                                      rand_keys.dtype in (torch.int32, torch.uint32)):
+        raise TypeError("rand_keys: expected a contiguous CUDA tensor of dtype int32 or uint32")
+    B, n = rewards.shape
+    records = list(records)
+    if outs is None:
+        outs = [torch.empty((B * max(m, 0),) + tuple(t.shape[2:]), dtype=t.dtype, device=t.device)
+                for t in records]
+    if len(outs) != len(records):
+        raise ValueError("outs: one tensor per record")
+    descr = (PodsRecord * max(len(records), 1))()
+    for q, (t, o) in enumerate(zip(records, outs)):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dim() >= 2
+                and tuple(t.shape[:2]) == (B, n)):
+            raise TypeError(f"records[{q}]: expected a contiguous CUDA tensor [B, n, ...]")
+        row_bytes = (t[0, 0].numel() if t.dim() > 2 else 1) * t.element_size()
+        if not (isinstance(o, torch.Tensor) and o.is_cuda and o.is_contiguous() and o.dtype == t.dtype
+                and o.numel() * o.element_size() == B * m * row_bytes):
+            raise TypeError(f"outs[{q}]: expected a contiguous CUDA tensor [B*m, ...] of records[{q}]'s dtype")
+        descr[q] = PodsRecord(t.data_ptr(), o.data_ptr(), row_bytes)
+    sel_idx = torch.empty((B, max(m, 0)), dtype=torch.int32, device=rewards.device)
+    sel_k = torch.empty((B,), dtype=torch.int32, device=rewards.device)
+    adv = torch.empty((B, max(m, 0)), dtype=torch.float32, device=rewards.device)
+    _check(load().pods_downsample_gather(_ptr(rewards), _ptr(rand_keys), B, n, m, int(rule), float(std_eps),
+                                         1 if stats_from_all else 0, descr, len(records), _ptr(sel_idx),
+                                         _ptr(sel_k), _ptr(adv), _stream(stream)))
+    return sel_idx, sel_k, adv, outs
 
 
 def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_eps: float,

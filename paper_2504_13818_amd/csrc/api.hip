@@ -125,6 +125,34 @@ pods_status pods_advantage_before(const float* rewards, const int32_t* sel_idx, 
     return advantage_entry("pods_advantage_before", rewards, sel_idx, B, n, m, std_eps, true, adv, stream);
 }
 
+pods_status pods_downsample_gather(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n,
+                                   int32_t m, pods_rule rule, float std_eps, int32_t stats_from_all,
+                                   const pods_record* records, int32_t num_records, int32_t* sel_idx,
+                                   int32_t* sel_k, float* adv, void* stream) {
+    const char* who = "pods_downsample_gather";
+    if (rule != PODS_RULE_MAXVAR && rule != PODS_RULE_MAXR && rule != PODS_RULE_PERC && rule != PODS_RULE_RAND)
+        return fail(PODS_ERR_INVALID_ARG, "%s: unknown rule %d", who, (int)rule);
+    if (rewards == nullptr || sel_idx == nullptr || adv == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "%s: rewards, sel_idx and adv must not be null", who);
+    if (rule == PODS_RULE_RAND && rand_keys == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "%s: the random rule needs rand_keys", who);
+    if (B <= 0 || n <= 0 || m <= 0)
+        return fail(PODS_ERR_INVALID_ARG, "%s: B=%d n=%d m=%d must be positive", who, B, n, m);
+    if (m > n) return fail(PODS_ERR_INVALID_ARG, "%s: m=%d exceeds n=%d", who, m, n);
+    if (n > 1024) return fail(PODS_ERR_UNSUPPORTED, "%s: n=%d exceeds 1024", who, n);
+    if (!(std_eps >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "%s: std_eps < 0", who);
+    if (num_records < 0 || num_records > PODS_MAX_RECORDS)
+        return fail(PODS_ERR_INVALID_ARG, "%s: num_records=%d outside [0, %d]", who, num_records,
+                    (int)PODS_MAX_RECORDS);
+    if (num_records > 0 && records == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "%s: records must not be null", who);
+    for (int32_t q = 0; q < num_records; ++q)
+        if (records[q].src == nullptr || records[q].dst == nullptr || records[q].row_bytes == 0)
+            return fail(PODS_ERR_INVALID_ARG, "%s: record %d has a null pointer or no bytes", who, q);
+    return launch_downsample_gather(rewards, rand_keys, B, n, m, (int32_t)rule, std_eps, stats_from_all != 0,
+                                    records, num_records, sel_idx, sel_k, adv, static_cast<hipStream_t>(stream));
+}
+
 static bool loss_sizes_ok(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt) {
     return R > 0 && T > 0 && d > 0 && V > 0 && (dt == PODS_F32 || dt == PODS_BF16) &&
            (int64_t)R * T <= (int64_t)1 << 30;
