@@ -317,6 +317,25 @@ def main():
                     path_executed_frac=4 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                     path_model_frac=3 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
 
+    # Beside the headline (which back-propagates every valid token): the same step with the rollouts
+    # of prompts without reward variance (advantage exactly 0) left out of the backward pass.
+    def step_skip():
+        lib.pods_select(rewards, m, sel_idx, sel_k)
+        lib.pods_advantage(rewards, sel_idx, 0.0, adv)
+        lib.grpo_token_loss_fwd_bwd(hidden, w, tokens, old_logp, adv.view(-1), lengths, c["clip_eps"],
+                                    1.0, workspace=ws, out=out, skip_zero_advantage=True)
+    skip_steps = max(3, args.steps // 4)
+    step_skip()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(skip_steps):
+        step_skip()
+    torch.cuda.synchronize()
+    skip_ms = (time.perf_counter() - t0) * 1e3 / skip_steps
+    live = int(lens_np[(adv.view(-1) != 0).cpu().numpy()].sum())
+    skip = dict(ms_per_step=skip_ms, steps=skip_steps, valid_tokens=n_valid, tokens_back_propagated=live,
+                note="not the headline: value counts every valid token and is measured without skipping")
+
     selector = time_selector(lib, torch, inputs, args.steps)
     result = {
         "metric": "GRPO token-loss fwd+bwd tokens/s (% MFMA peak); pods_select groups/s (% HBM)",
@@ -333,6 +352,7 @@ def main():
         "kernels": kernels,
         "selector": selector,
         "gather": time_gather(lib, torch, args.steps),
+        "skip_zero_advantage": skip,
         "loss": loss_val,
     }
     if not args.no_cpu_baseline:

@@ -19,6 +19,7 @@
  *                             projection, log-softmax, importance ratio, clipped surrogate, and
  *                             the gradients w.r.t. the hidden states and the lm_head weight,
  *                             without ever holding the [tokens, vocab] logits in memory.
+ *                             (_accumulate: d_w_lm +=; _kl: with a KL penalty; _ex: every option)
  *
  * Conventions for every entry point
  *   - Every pointer is a DEVICE pointer unless marked "host".  `stream` is a hipStream_t passed
@@ -239,6 +240,28 @@ pods_status grpo_token_loss_fwd_bwd_kl(const void* hidden, const void* w_lm, con
                                        int32_t accumulate_d_w, float* loss, float* logp_out,
                                        float* d_hidden, float* d_w_lm, void* workspace,
                                        size_t workspace_bytes, void* stream);
+
+/* The general form: every option of the three entry points above, plus the skipping of rollouts that
+ * cannot contribute to the gradients.
+ *
+ *   ref_logp, kl_coef  as in grpo_token_loss_fwd_bwd_kl; ref_logp may be NULL when kl_coef == 0
+ *   flags              PODS_LOSS_ACCUMULATE_D_W: d_w_lm += gradient.
+ *                      PODS_LOSS_SKIP_ZERO_ADVANTAGE: a rollout with a_i == 0 (every kept rollout of a
+ *                      prompt whose kept rewards are all equal, Sec. 3.2) has the per-token weight zero at
+ *                      every position, so its terms of both gradients vanish identically; with this flag
+ *                      the backward pass leaves those rollouts out (their d_hidden rows are written as
+ *                      zero) instead of multiplying by zero.  The loss, logp_out and, up to the order of
+ *                      floating-point summation over tokens in d_w_lm, the gradients are unchanged.  The
+ *                      flag is ignored while a KL penalty is active (kl_coef != 0), because the penalty
+ *                      gives such rollouts a gradient.
+ */
+enum { PODS_LOSS_ACCUMULATE_D_W = 1, PODS_LOSS_SKIP_ZERO_ADVANTAGE = 2 };
+pods_status grpo_token_loss_fwd_bwd_ex(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                       const float* old_logp, const float* ref_logp, const float* adv,
+                                       const int32_t* lengths, int32_t R, int32_t T, int32_t d, int32_t V,
+                                       pods_dtype dt, float clip_eps, float kl_coef, float grad_scale,
+                                       int32_t flags, float* loss, float* logp_out, float* d_hidden,
+                                       float* d_w_lm, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Per-launch timing for benchmarks (not part of the method).  pods_profile_enable(1) makes every
  * later library call on this thread bracket each of its kernel launches with a pair of HIP events

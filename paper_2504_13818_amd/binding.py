@@ -10,8 +10,10 @@ _lib = None
 
 PODS_F32, PODS_BF16 = 0, 1
 PODS_RULE_MAXVAR, PODS_RULE_MAXR, PODS_RULE_PERC, PODS_RULE_RAND = 0, 1, 2, 3
+PODS_LOSS_ACCUMULATE_D_W, PODS_LOSS_SKIP_ZERO_ADVANTAGE = 1, 2
 EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_advantage_before",
                     "pods_gather_rows", "pods_downsample_gather", "grpo_token_loss_fwd_bwd_accumulate", "grpo_token_loss_fwd_bwd_kl",
+                    "grpo_token_loss_fwd_bwd_ex",
                     "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
@@ -66,6 +68,8 @@ def load():
     lib.grpo_token_loss_fwd_bwd_kl.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                                ctypes.c_int, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp, _vp, _sz,
                                                _vp]
+    lib.grpo_token_loss_fwd_bwd_ex.restype = ctypes.c_int
+    lib.grpo_token_loss_fwd_bwd_ex.argtypes = list(lib.grpo_token_loss_fwd_bwd_kl.argtypes)
     lib.pods_gather_rows.restype = ctypes.c_int
     lib.pods_gather_rows.argtypes = [_vp, _vp, _i32, _i32, _i32, _sz, _vp, _vp]
     lib.pods_downsample_gather.restype = ctypes.c_int
@@ -255,13 +259,15 @@ def pods_downsample_gather(rewards, m: int, records=(), rule: int = PODS_RULE_MA
 def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_eps: float,
                             grad_scale: float = 1.0, workspace=None, want_logp: bool = True,
                             out=None, stream=None, accumulate_d_w: bool = False, ref_logp=None,
-                            kl_coef: float = 0.0):
+                            kl_coef: float = 0.0, skip_zero_advantage: bool = False):
     """Returns dict(loss[1], logp[R, T] or None, d_hidden[R, T, d], d_w_lm[V, d]), float32 on device.
 
     `workspace` is a uint8 CUDA tensor (allocated at the recommended size when None); `out` may
     carry preallocated loss / logp / d_hidden / d_w_lm tensors.  With accumulate_d_w the gradient is
     added to out["d_w_lm"] (grpo_token_loss_fwd_bwd_accumulate).  With ref_logp[R, T] float32 the KL
-    penalty kl_coef * KL is subtracted from every token's term (grpo_token_loss_fwd_bwd_kl).
+    penalty kl_coef * KL is subtracted from every token's term (grpo_token_loss_fwd_bwd_kl).  With
+    skip_zero_advantage the backward pass leaves out rollouts whose advantage is zero
+    (grpo_token_loss_fwd_bwd_ex).
     """
     import torch
     dt = _dt(hidden)
@@ -291,6 +297,16 @@ def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_e
                                 device=dev)
     if ref_logp is not None:
         _need(ref_logp, torch.float32, "ref_logp")
+    if skip_zero_advantage:
+        _check(load().grpo_token_loss_fwd_bwd_ex(
+            _ptr(hidden), _ptr(w_lm), _ptr(tokens), _ptr(old_logp), _ptr(ref_logp), _ptr(adv), _ptr(lengths), R, T,
+            d, V, dt, float(clip_eps), float(kl_coef), float(grad_scale),
+            PODS_LOSS_SKIP_ZERO_ADVANTAGE | (PODS_LOSS_ACCUMULATE_D_W if accumulate_d_w else 0),
+            _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["d_hidden"]), _ptr(out["d_w_lm"]), _ptr(workspace),
+            workspace.numel(), _stream(stream)))
+        out["workspace"] = workspace
+        return out
+    if ref_logp is not None:
         _check(load().grpo_token_loss_fwd_bwd_kl(
             _ptr(hidden), _ptr(w_lm), _ptr(tokens), _ptr(old_logp), _ptr(ref_logp), _ptr(adv), _ptr(lengths), R, T,
             d, V, dt, float(clip_eps), float(kl_coef), float(grad_scale), 1 if accumulate_d_w else 0,

@@ -173,7 +173,7 @@ static pods_status token_loss_entry(const void* hidden, const void* w_lm, const 
                                     const float* adv, const int32_t* lengths,
                                     int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
                                     float clip_eps, float grad_scale, float* loss, float* logp_out,
-                                    float* d_hidden, float* d_w_lm, bool accumulate_d_w, void* workspace,
+                                    float* d_hidden, float* d_w_lm, int32_t flags, void* workspace,
                                     size_t workspace_bytes, void* stream) {
     if (hidden == nullptr || w_lm == nullptr || tokens == nullptr || old_logp == nullptr ||
         adv == nullptr || loss == nullptr || d_hidden == nullptr || d_w_lm == nullptr)
@@ -184,6 +184,8 @@ static pods_status token_loss_entry(const void* hidden, const void* w_lm, const 
     if (dt != PODS_F32 && dt != PODS_BF16)
         return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: unknown dtype %d", (int)dt);
     if (!(clip_eps >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: clip_eps < 0");
+    if ((flags & ~(PODS_LOSS_ACCUMULATE_D_W | PODS_LOSS_SKIP_ZERO_ADVANTAGE)) != 0)
+        return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: unknown flag bits in %d", flags);
     if (!(grad_scale == grad_scale)) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd: grad_scale is NaN");
     if (!loss_sizes_ok(R, T, d, V, dt))
         return fail(PODS_ERR_UNSUPPORTED, "grpo_token_loss_fwd_bwd: R*T exceeds 2^30 positions");
@@ -200,7 +202,10 @@ static pods_status token_loss_entry(const void* hidden, const void* w_lm, const 
     a.ref_logp = (ref_logp != nullptr && kl_coef != 0.0f) ? ref_logp : nullptr; a.kl_coef = kl_coef;
     a.lengths = lengths; a.R = R; a.T = T; a.d = d; a.V = V; a.dt = dt; a.clip_eps = clip_eps;
     a.grad_scale = grad_scale; a.loss = loss; a.logp_out = logp_out; a.d_hidden = d_hidden;
-    a.d_w_lm = d_w_lm; a.accumulate_d_w = accumulate_d_w; a.workspace = static_cast<unsigned char*>(workspace);
+    a.d_w_lm = d_w_lm; a.accumulate_d_w = (flags & PODS_LOSS_ACCUMULATE_D_W) != 0;
+    // with a KL penalty a zero-advantage rollout still has a gradient: nothing can be skipped
+    a.skip_zero_adv = (flags & PODS_LOSS_SKIP_ZERO_ADVANTAGE) != 0 && a.ref_logp == nullptr;
+    a.workspace = static_cast<unsigned char*>(workspace);
     a.workspace_bytes = workspace_bytes; a.stream = static_cast<hipStream_t>(stream);
     return run_loss(a);
 }
@@ -212,7 +217,7 @@ pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const 
                                     float* d_hidden, float* d_w_lm, void* workspace,
                                     size_t workspace_bytes, void* stream) {
     return token_loss_entry(hidden, w_lm, tokens, old_logp, nullptr, 0.0f, adv, lengths, R, T, d, V, dt, clip_eps,
-                            grad_scale, loss, logp_out, d_hidden, d_w_lm, false, workspace, workspace_bytes, stream);
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm, 0, workspace, workspace_bytes, stream);
 }
 
 pods_status grpo_token_loss_fwd_bwd_accumulate(const void* hidden, const void* w_lm, const int32_t* tokens,
@@ -223,7 +228,7 @@ pods_status grpo_token_loss_fwd_bwd_accumulate(const void* hidden, const void* w
                                                float* d_w_lm, void* workspace, size_t workspace_bytes,
                                                void* stream) {
     return token_loss_entry(hidden, w_lm, tokens, old_logp, nullptr, 0.0f, adv, lengths, R, T, d, V, dt, clip_eps,
-                            grad_scale, loss, logp_out, d_hidden, d_w_lm, true, workspace, workspace_bytes, stream);
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm, PODS_LOSS_ACCUMULATE_D_W, workspace, workspace_bytes, stream);
 }
 
 pods_status grpo_token_loss_fwd_bwd_kl(const void* hidden, const void* w_lm, const int32_t* tokens,
@@ -236,8 +241,21 @@ pods_status grpo_token_loss_fwd_bwd_kl(const void* hidden, const void* w_lm, con
     if (ref_logp == nullptr) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_kl: ref_logp is null");
     if (!(kl_coef >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_kl: kl_coef < 0");
     return token_loss_entry(hidden, w_lm, tokens, old_logp, ref_logp, kl_coef, adv, lengths, R, T, d, V, dt, clip_eps,
-                            grad_scale, loss, logp_out, d_hidden, d_w_lm, accumulate_d_w != 0, workspace,
-                            workspace_bytes, stream);
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm,
+                            accumulate_d_w != 0 ? PODS_LOSS_ACCUMULATE_D_W : 0, workspace, workspace_bytes, stream);
+}
+
+pods_status grpo_token_loss_fwd_bwd_ex(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                       const float* old_logp, const float* ref_logp, const float* adv,
+                                       const int32_t* lengths, int32_t R, int32_t T, int32_t d, int32_t V,
+                                       pods_dtype dt, float clip_eps, float kl_coef, float grad_scale,
+                                       int32_t flags, float* loss, float* logp_out, float* d_hidden,
+                                       float* d_w_lm, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!(kl_coef >= 0.0f)) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_ex: kl_coef < 0");
+    if (ref_logp == nullptr && kl_coef != 0.0f)
+        return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_ex: kl_coef = %g needs ref_logp", (double)kl_coef);
+    return token_loss_entry(hidden, w_lm, tokens, old_logp, ref_logp, kl_coef, adv, lengths, R, T, d, V, dt, clip_eps,
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm, flags, workspace, workspace_bytes, stream);
 }
 
 pods_status pods_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,

@@ -3,8 +3,8 @@
 //
 // Notation: R kept rollouts, T padded length, N = sum of lengths (valid token positions, known
 // only on the device), d hidden size, V vocabulary.  Valid positions are packed into rows
-// p = 0..N-1 (rollout-major); every kernel is launched for the worst case R*T rows and returns
-// early for rows at or beyond N.
+// p = 0..N-1 (rollout-major; when zero-advantage rollouts are skipped, the others first); every
+// kernel is launched for the worst case R*T rows and returns early for rows at or beyond N.
 #pragma once
 
 #include "common.h"
@@ -28,6 +28,7 @@ struct LossArgs {
     float* d_hidden;
     float* d_w_lm;
     bool accumulate_d_w;   // d_w_lm += gradient instead of d_w_lm = gradient
+    bool skip_zero_adv;    // rollouts with a_i == 0 take no part in the backward pass
     unsigned char* workspace;
     size_t workspace_bytes;
     hipStream_t stream;
@@ -37,7 +38,9 @@ struct LossArgs {
 struct LossHeader {
     int32_t n_valid;     // N
     uint32_t gmax_bits;  // bit pattern of max_t |g_t| (non-negative floats order as integers)
-    int32_t pad[62];
+    int32_t n_bwd;       // packed rows the backward pass covers: N, or only the rows of rollouts with
+                         // a non-zero advantage (they are packed first when those are skipped)
+    int32_t pad[61];
 };
 
 // Scale 2^-floor(log2 gmax) that brings the per-token weights g_t into [0, 2).

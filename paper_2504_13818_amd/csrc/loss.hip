@@ -93,8 +93,12 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
 
 namespace {
 
-// Exclusive prefix sum of the rollout lengths: offsets[i] = first packed row of rollout i.
+// Exclusive prefix sum of the rollout lengths: offsets[i] = first packed row of rollout i.  With
+// `skip`, rollouts whose advantage is non-zero are packed first (one pass for them, one for the
+// rest) and the backward pass stops after them: a zero advantage makes every per-token weight of
+// the rollout zero, so its gradient terms vanish identically.
 __global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t* __restrict__ lengths,
+                                                            const float* __restrict__ adv, int skip,
                                                             int R, int T,
                                                             int32_t* __restrict__ offsets,
                                                             LossHeader* __restrict__ hdr) {
@@ -103,28 +107,34 @@ __global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t* __res
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) carry = 0;
     __syncthreads();
-    for (int base = 0; base < R; base += 1024) {
-        const int i = base + tid;
-        int32_t len = 0;
-        if (i < R) len = lengths ? lengths[i] : T;
-        int32_t x = len;
+    int32_t n_live = 0;
+    for (int pass = 0; pass < (skip ? 2 : 1); ++pass) {
+        for (int base = 0; base < R; base += 1024) {
+            const int i = base + tid;
+            const bool mine = i < R && (!skip || ((adv[i] != 0.0f) == (pass == 0)));
+            int32_t len = 0;
+            if (mine) len = lengths ? lengths[i] : T;
+            int32_t x = len;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            int32_t t = __shfl_up(x, off, 64);
-            if (lane >= off) x += t;
+            for (int off = 1; off < 64; off <<= 1) {
+                int32_t t = __shfl_up(x, off, 64);
+                if (lane >= off) x += t;
+            }
+            if (lane == 63) wave_tot[wave] = x;
+            __syncthreads();
+            int32_t before = carry;
+            for (int w = 0; w < wave; ++w) before += wave_tot[w];
+            if (mine) offsets[i] = before + x - len;
+            __syncthreads();
+            if (tid == 1023) carry = before + x;
+            __syncthreads();
         }
-        if (lane == 63) wave_tot[wave] = x;
-        __syncthreads();
-        int32_t before = carry;
-        for (int w = 0; w < wave; ++w) before += wave_tot[w];
-        if (i < R) offsets[i] = before + x - len;
-        __syncthreads();
-        if (tid == 1023) carry = before + x;
-        __syncthreads();
+        if (pass == 0) n_live = carry;
     }
     if (tid == 0) {
         offsets[R] = carry;
         hdr->n_valid = carry;
+        hdr->n_bwd = skip ? n_live : carry;
         hdr->gmax_bits = 0u;
     }
 }
@@ -150,13 +160,15 @@ __global__ __launch_bounds__(256) void fill_rows_kernel(const int32_t* __restric
     }
 }
 
-// d_hidden rows of padded positions are zero.
+// d_hidden rows of padded positions, and of rollouts the backward pass skips, are zero.
 __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __restrict__ lengths,
+                                                            const float* __restrict__ adv, int skip,
                                                             int T, int d,
                                                             float* __restrict__ d_hidden) {
     const int64_t flat = blockIdx.x;
     const int i = (int)(flat / T), t = (int)(flat % T);
-    if (t < lengths[i]) return;
+    const int len = lengths ? lengths[i] : T;
+    if (t < len && !(skip && adv[i] == 0.0f)) return;
     float* row = d_hidden + flat * d;
     if ((d & 3) == 0) {
         float4* r4 = reinterpret_cast<float4*>(row);
@@ -265,15 +277,15 @@ pods_status run_loss(const LossArgs& a) {
     auto* loss_part = reinterpret_cast<double*>(ws + p.off_losspart);
     pods_status st;
 
-    PODS_LAUNCH("scan_lengths", a.stream, scan_lengths_kernel, dim3(1), dim3(1024), 0, a.stream, a.lengths, a.R, a.T,
-                       offsets, hdr);
+    PODS_LAUNCH("scan_lengths", a.stream, scan_lengths_kernel, dim3(1), dim3(1024), 0, a.stream, a.lengths, a.adv,
+                       a.skip_zero_adv ? 1 : 0, a.R, a.T, offsets, hdr);
     if ((st = check_launch("scan_lengths")) != PODS_OK) return st;
     PODS_LAUNCH("fill_rows", a.stream, fill_rows_kernel, dim3((unsigned)a.R, (unsigned)ceil_div(a.T, 256)), dim3(256),
                        0, a.stream, a.lengths, a.tokens, offsets, a.T, row_map, tok, a.logp_out);
     if ((st = check_launch("fill_rows")) != PODS_OK) return st;
-    if (a.lengths != nullptr) {
+    if (a.lengths != nullptr || a.skip_zero_adv) {
         PODS_LAUNCH("zero_pad_rows", a.stream, zero_pad_rows_kernel, dim3((unsigned)p.ncap), dim3(256), 0, a.stream,
-                           a.lengths, a.T, a.d, a.d_hidden);
+                           a.lengths, a.adv, a.skip_zero_adv ? 1 : 0, a.T, a.d, a.d_hidden);
         if ((st = check_launch("zero_pad_rows")) != PODS_OK) return st;
     }
 

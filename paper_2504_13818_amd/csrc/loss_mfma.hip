@@ -501,7 +501,7 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
     const uint16_t* __restrict__ wt, int d, int V, int v0, int vc, int ntt_grid, int64_t ldq,
     _Float16* __restrict__ q) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const int n_valid = hdr->n_valid;
+    const int n_valid = hdr->n_bwd;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
     int64_t tt, vt;
     if (!decode_tile(blockIdx.x, ntt_grid, vc / kTile, tt, vt) || tt >= ntt) return;
@@ -591,7 +591,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
                                                     const uint16_t* __restrict__ q, int64_t ldq, int d,
                                                     int V, int v0, int vc, int ntt_grid, float* __restrict__ d_hidden) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const int n_valid = hdr->n_valid;
+    const int n_valid = hdr->n_bwd;
     const int64_t ntt = (n_valid + kTile - 1) / kTile;
     int64_t tt, kt0;
     if (!decode_tile(blockIdx.x, ntt_grid, (d + kTile - 1) / kTile, tt, kt0) || tt >= ntt) return;
@@ -670,7 +670,7 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
                                                     int d, int V, int v0, int vc, int accumulate,
                                                     float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const int n_valid = hdr->n_valid;
+    const int n_valid = hdr->n_bwd;
     int64_t vt, kt0;
     if (!decode_tile(blockIdx.x, vc / kTile, (d + kTile - 1) / kTile, vt, kt0)) return;
     if ((int64_t)v0 + vt * kTile >= V) return;
@@ -718,7 +718,7 @@ __global__ __launch_bounds__(256) void dh_onehot_kernel(const LossHeader* __rest
                                                         const uint16_t* __restrict__ w, int d,
                                                         float* __restrict__ d_hidden) {
     const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // one wave per token
-    if (p >= hdr->n_valid) return;
+    if (p >= hdr->n_bwd) return;
     const int lane = threadIdx.x & 63;
     const float c = coef[p];
     const uint16_t* wrow = w + (int64_t)tok[p] * d;
@@ -746,7 +746,7 @@ __global__ __launch_bounds__(256) void dw_onehot_kernel(const LossHeader* __rest
                                                         const float* __restrict__ coef,
                                                         const uint16_t* __restrict__ hidden, int d,
                                                         int V, float* __restrict__ d_w) {
-    const int n_valid = hdr->n_valid;
+    const int n_valid = hdr->n_bwd;
     const int lane = threadIdx.x & 63;
     const int v_lo = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kOnehotRows;
     if (v_lo >= V) return;
@@ -838,7 +838,7 @@ __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restri
     int64_t nrows = rows, fill_to = rows_out;
     float common = kWScale;
     if (token_rows) {
-        nrows = hdr->n_valid;
+        nrows = hdr->n_bwd;
         fill_to = (nrows + kTile - 1) / kTile * kTile;
         common = g_range_scale(hdr);
     }

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void simple_dh_kernel(const LossHeader* __rest
     float* acc = lds + d;       // [d]
     float* dzs = lds + 2 * d;   // [kChunk]
     const int p = blockIdx.x;
-    if (p >= hdr->n_valid) return;
+    if (p >= hdr->n_bwd) return;
     const size_t hrow = (size_t)row_map[p] * d;
     const float gp = g[p];
     if (gp == 0.0f) {  // clipped token or zero advantage: exact zero row
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void simple_dw_kernel(const LossHeader* __rest
     float* acc = lds + d;       // [d]
     float* dzs = lds + 2 * d;   // [kChunk]
     const int v = blockIdx.x;
-    const int n_valid = hdr->n_valid;
+    const int n_valid = hdr->n_bwd;
     const size_t wrow = (size_t)v * d;
     for (int k = threadIdx.x; k < d; k += 256) { ws[k] = load_elem(w, wrow + k); acc[k] = 0.0f; }
     __syncthreads();
