@@ -101,3 +101,40 @@ def test_skip_flag_checks(pods):
     assert lib.grpo_token_loss_fwd_bwd_ex(*args(0, 0.1)) == 1           # KL coefficient without ref_logp
     assert lib.grpo_token_loss_fwd_bwd_ex(*args(3, 0.0)) == 0
     torch.cuda.synchronize()
+
+
+def test_skip_at_full_size_matches_the_plain_call(pods):
+    """Config 1 at the benchmark's size and launch configuration: with the flag, d_hidden and the
+    log-probs are the plain call's bit for bit, d_w_lm agrees to summation order, and the rows of
+    zero-advantage rollouts are exact zeros."""
+    import bench
+    from paper_2504_13818_amd import inputs
+    cfg = 1
+    c = inputs.CONFIGS[cfg]
+    B, m, T, d, V = c["B"], c["m"], c["T"], c["d"], c["V"]
+    R = B * m
+    dev = torch.device("cuda:0")
+    rewards = torch.from_numpy(inputs.rewards(cfg)).to(dev)
+    lengths = torch.from_numpy(inputs.lengths(cfg)).to(dev)
+    tokens = torch.from_numpy(inputs.tokens(cfg, R, T, V)).to(dev)
+    hidden, w = inputs.dense_torch(cfg, dev)
+    cur = bench.current_logp_torch(torch, hidden, w, tokens)
+    g = torch.Generator(device=dev)
+    g.manual_seed(inputs.seed_for(cfg, 5))
+    old_logp = (cur + 0.05 * torch.randn(cur.shape, generator=g, device=dev)).contiguous()
+    del cur
+    sel, _ = pods.pods_select(rewards, m)
+    adv = pods.pods_advantage(rewards, sel).view(-1)
+    dead = adv == 0
+    assert 0 < int(dead.sum()) < R                                    # the config has prompts without reward variance
+    plain = pods.grpo_token_loss_fwd_bwd(hidden, w, tokens, old_logp, adv, lengths, c["clip_eps"])
+    ws = plain.pop("workspace")
+    skip = pods.grpo_token_loss_fwd_bwd(hidden, w, tokens, old_logp, adv, lengths, c["clip_eps"], workspace=ws,
+                                        skip_zero_advantage=True)
+    torch.cuda.synchronize()
+    assert torch.equal(skip["logp"], plain["logp"])
+    assert torch.equal(skip["d_hidden"], plain["d_hidden"])
+    assert float(skip["d_hidden"][dead].abs().max()) == 0.0
+    assert float(skip["loss"]) == pytest.approx(float(plain["loss"]), rel=1e-6, abs=1e-12)
+    diff = float((skip["d_w_lm"].double() - plain["d_w_lm"].double()).norm())
+    assert diff <= 1e-5 * float(plain["d_w_lm"].double().norm())
