@@ -526,57 +526,64 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
     // as [token][vocabulary] rows (pitch 520 B: the 32 rows a half-wave writes fall into 32 different
     // bank pairs) every later store instruction covers two whole 512-byte rows.
     __builtin_amdgcn_s_barrier();   // every wave has left the operand ring
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
-        const int64_t p = tt * kTile + tloc;
-        const bool valid = p < n_valid;
-        const int y = valid ? tok[p] : -1;
-        // kQScale softmax = 2^(z log2e - lse log2e + 14); rows past N get 2^-inf = 0
-        const float off = valid ? fmaf(-lse[p], kLog2e, kLog2Q) : -__builtin_huge_valf();
-        float val[4][16];
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                val[mi][r] = __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e, off));
-        const int slot = acc_slot_of(y - vbase);
-        if (__any(slot >= 0)) {
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (slot == mi * 16 + r) val[mi][r] = 0.0f;  // the y logit is handled in fp32
-        }
-        if (partial) {
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (vbase + mi * 32 + 8 * (r >> 2) + (r & 3) >= V) val[mi][r] = 0.0f;
-        }
-        unsigned char* row = lds + tloc * kQPitch + vtile * 2;
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                f16x4 pk;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) pk[c] = (_Float16)val[mi][b * 4 + c];
-                *reinterpret_cast<f16x4*>(row + (mi * 32 + 8 * b) * 2) = pk;
-            }
-    }
-    __syncthreads();
-    // wave w stores token rows 64 w .. 64 w + 63 of the tile, two rows (2 x 512 B) per instruction
     _Float16* qtile = q + (tt * kTile) * ldq + vt * kTile;
+    // Two passes over the tile's tokens (MFMA block columns 0-1, then 2-3 of each wave): the stores of the
+    // first pass drain while the second pass computes its exponentials.
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj) {
+            const int ni = 2 * pass + nj;
+            const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
+            const int64_t p = tt * kTile + tloc;
+            const bool valid = p < n_valid;
+            const int y = valid ? tok[p] : -1;
+            // kQScale softmax = 2^(z log2e - lse log2e + 14); rows past N get 2^-inf = 0
+            const float off = valid ? fmaf(-lse[p], kLog2e, kLog2Q) : -__builtin_huge_valf();
+            float val[4][16];
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    val[mi][r] = __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e, off));
+            const int slot = acc_slot_of(y - vbase);
+            if (__any(slot >= 0)) {
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (slot == mi * 16 + r) val[mi][r] = 0.0f;  // the y logit is handled in fp32
+            }
+            if (partial) {
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (vbase + mi * 32 + 8 * (r >> 2) + (r & 3) >= V) val[mi][r] = 0.0f;
+            }
+            unsigned char* row = lds + tloc * kQPitch + vtile * 2;
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    f16x4 pk;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) pk[c] = (_Float16)val[mi][b * 4 + c];
+                    *reinterpret_cast<f16x4*>(row + (mi * 32 + 8 * b) * 2) = pk;
+                }
+        }
+        __syncthreads();
+        // this pass filled token rows 128 h + 64 pass .. + 63 (h = 0, 1); wave w stores 32 of them, two rows
+        // (2 x 512 B) per instruction
 #pragma unroll 4
-    for (int i = 0; i < 32; ++i) {
-        const int r = g.wave * 64 + 2 * i + (g.lane >> 5);
-        const unsigned char* src = lds + r * kQPitch + (g.lane & 31) * 16;
-        const f16x4 lo = *reinterpret_cast<const f16x4*>(src);
-        const f16x4 hi = *reinterpret_cast<const f16x4*>(src + 8);
-        const f16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        *reinterpret_cast<f16x8*>(qtile + (int64_t)r * ldq + (g.lane & 31) * 8) = both;
+        for (int i = 0; i < 16; ++i) {
+            const int r = (g.wave >> 1) * 128 + pass * 64 + (g.wave & 1) * 32 + 2 * i + (g.lane >> 5);
+            const unsigned char* src = lds + r * kQPitch + (g.lane & 31) * 16;
+            const f16x4 lo = *reinterpret_cast<const f16x4*>(src);
+            const f16x4 hi = *reinterpret_cast<const f16x4*>(src + 8);
+            const f16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            *reinterpret_cast<f16x8*>(qtile + (int64_t)r * ldq + (g.lane & 31) * 8) = both;
+        }
     }
 }
 
