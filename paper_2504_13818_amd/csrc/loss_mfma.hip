@@ -619,6 +619,24 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     // into different banks), every global load and store covers one whole 1 KiB row segment.
     for (int half = 0; half < 2; ++half) {
         __syncthreads();   // the ring (first pass) or the previous half has been consumed
+        // wave w updates rows 32 w .. 32 w + 31 of this half in four batches of eight rows; a batch's
+        // d_hidden values are requested one batch ahead (the first before the staging below), so that
+        // their latency is covered by the staging and by the previous batch's additions and stores
+        const int64_t p0 = tt * kTile + half * 128 + g.wave * 32;
+        const int live = (int)(n_valid - p0 < 32 ? (n_valid - p0 < 0 ? 0 : n_valid - p0) : 32);   // rows are in token order
+        const int my_row = (g.lane < live) ? row_map[p0 + g.lane] : 0;
+        const int k = (int)kt0 * kTile + g.lane * 4;
+        const bool cols = k < d;
+        f32x4 cur[2][8];
+        auto row_ptr = [&](int i) {   // row i of this wave's 32; past the end: the batch's first row
+            const int src_lane = i < live ? i : (i & ~7);
+            const int64_t row = __builtin_amdgcn_readlane(my_row, src_lane);
+            return reinterpret_cast<f32x4*>(d_hidden + row * d + k);
+        };
+        if (cols && live > 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) cur[0][j] = *row_ptr(j);
+        }
         if (g.wn == half) {
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni) {
@@ -638,28 +656,21 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
             }
         }
         __syncthreads();
-        // wave w updates rows 32 w .. 32 w + 31 of this half, eight rows in flight at a time
-        const int64_t p0 = tt * kTile + half * 128 + g.wave * 32;
-        const int live = (int)(n_valid - p0 < 32 ? (n_valid - p0 < 0 ? 0 : n_valid - p0) : 32);   // rows are in token order
-        const int my_row = (g.lane < live) ? row_map[p0 + g.lane] : 0;
-        const int k = (int)kt0 * kTile + g.lane * 4;
-        if (k < d) {
-            for (int i0 = 0; i0 < live; i0 += 8) {
-                f32x4* dst[8];
-                f32x4 cur[8];
+        if (cols) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int src_lane = i0 + j < live ? i0 + j : i0;   // past the end: a row already in flight
-                    const int64_t row = __builtin_amdgcn_readlane(my_row, src_lane);
-                    dst[j] = reinterpret_cast<f32x4*>(d_hidden + row * d + k);
-                    cur[j] = *dst[j];
-                }
+            for (int b = 0; b < 4; ++b) {
+                if (8 * b < live) {
+                    if (b + 1 < 4 && 8 * (b + 1) < live) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if (i0 + j < live) {
-                        const int r = g.wave * 32 + i0 + j;
-                        const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * kHPitch + g.lane * 16);
-                        *dst[j] = v + cur[j];
+                        for (int j = 0; j < 8; ++j) cur[(b + 1) & 1][j] = *row_ptr(8 * (b + 1) + j);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        if (8 * b + j < live) {
+                            const int r = g.wave * 32 + 8 * b + j;
+                            const f32x4 v = *reinterpret_cast<const f32x4*>(lds + r * kHPitch + g.lane * 16);
+                            *row_ptr(8 * b + j) = v + cur[b & 1][j];
+                        }
                     }
                 }
             }
