@@ -223,7 +223,7 @@ def main():
         return
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
-              "(groups and rollouts shard across GPUs without exchange; see DESIGN.md).", file=sys.stderr)
+              "(prompt groups and kept rollouts shard across GPUs without exchange; only d_w_lm is reduced).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
