@@ -172,6 +172,11 @@ pods_status pods_downsample_gather(const float* rewards, const uint32_t* rand_ke
  * sizes. */
 size_t grpo_token_loss_workspace_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
 size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
+/* Bytes of a workspace of workspace_bytes that a call with these sizes lays its working arrays out in
+ * (never more than workspace_bytes; host arithmetic only).  Returns 0 for invalid sizes or a
+ * workspace below the minimum. */
+size_t grpo_token_loss_workspace_used_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
+                                            size_t workspace_bytes);
 
 /* GRPO-PODS token loss, forward and backward (objective of Sec. 3.2; with S = all rollouts it
  * is L_GRPO of Sec. 3.1).  For R kept rollouts (R = B*m over a batch of prompts, concatenated

@@ -15,7 +15,8 @@ EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_ad
                     "pods_gather_rows", "pods_downsample_gather", "grpo_token_loss_fwd_bwd_accumulate", "grpo_token_loss_fwd_bwd_kl",
                     "grpo_token_loss_fwd_bwd_ex",
                     "grpo_token_loss_workspace_bytes",
-                    "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_fwd_bwd",
+                    "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_workspace_used_bytes",
+                    "grpo_token_loss_fwd_bwd",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
 
 _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
@@ -59,6 +60,8 @@ def load():
         f = getattr(lib, name)
         f.restype = _sz
         f.argtypes = [_i32, _i32, _i32, _i32, ctypes.c_int]
+    lib.grpo_token_loss_workspace_used_bytes.restype = _sz
+    lib.grpo_token_loss_workspace_used_bytes.argtypes = [_i32, _i32, _i32, _i32, ctypes.c_int, _sz]
     for name in ("grpo_token_loss_fwd_bwd", "grpo_token_loss_fwd_bwd_accumulate"):
         f = getattr(lib, name)
         f.restype = ctypes.c_int
@@ -197,6 +200,10 @@ def grpo_token_loss_workspace_bytes(R, T, d, V, dt) -> int:
 
 def grpo_token_loss_workspace_min_bytes(R, T, d, V, dt) -> int:
     return int(load().grpo_token_loss_workspace_min_bytes(R, T, d, V, dt))
+
+
+def grpo_token_loss_workspace_used_bytes(R, T, d, V, dt, workspace_bytes) -> int:
+    return int(load().grpo_token_loss_workspace_used_bytes(R, T, d, V, dt, workspace_bytes))
 
 
 def pods_gather_rows(per_rollout, sel_idx, out=None, stream=None):

@@ -168,6 +168,13 @@ size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int3
     return plan_loss(R, T, d, V, dt, 1).total;
 }
 
+size_t grpo_token_loss_workspace_used_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
+                                            size_t workspace_bytes) {
+    if (!loss_sizes_ok(R, T, d, V, dt)) return 0;
+    if (workspace_bytes < plan_loss(R, T, d, V, dt, 1).total) return 0;
+    return plan_loss(R, T, d, V, dt, workspace_bytes).total;
+}
+
 static pods_status token_loss_entry(const void* hidden, const void* w_lm, const int32_t* tokens,
                                     const float* old_logp, const float* ref_logp, float kl_coef,
                                     const float* adv, const int32_t* lengths,

@@ -72,20 +72,20 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     } else if (mode == 1) {
         vc = kTile;
     } else {
+        // A caller-given workspace at least as large as the recommendation gets the recommended chunk.
+        // Below it: the largest chunk (at most four default chunks) whose layout fits.  The layout is not
+        // monotone in the chunk (the fp16 weight copy has nchunks * vc rows, which can grow when vc
+        // shrinks), so every candidate is laid out and checked; vc = kTile is the minimum the entry point
+        // has already checked against.
+        const LossPlan rec = plan_loss(R, T, d, V, dt, 0);
+        if (rec.total <= mode) return rec;
+        const int64_t cap = vround < 4 * kDefaultVocabChunk ? vround : 4 * kDefaultVocabChunk;
         vc = kTile;
         LossPlan q = p;
-        // largest multiple of kTile (at most the whole rounded vocabulary) that fits in `mode` bytes
-        int lo = 1, hi = (int)(vround / kTile);
-        while (lo < hi) {
-            int mid = (lo + hi + 1) / 2;
-            total_for(mid * kTile, q);
-            if (q.total <= mode) lo = mid; else hi = mid - 1;
+        for (int64_t c = cap; c > kTile; c -= kTile) {
+            total_for((int)c, q);
+            if (q.total <= mode) { vc = (int)c; break; }
         }
-        vc = lo * kTile;
-        if (vc > 4 * kDefaultVocabChunk) vc = 4 * kDefaultVocabChunk;
-        // a caller-given workspace at least as large as the recommendation gets the recommended chunk
-        LossPlan rec = plan_loss(R, T, d, V, dt, 0);
-        if (rec.total <= mode && rec.vc <= vc) vc = rec.vc;
     }
     total_for(vc, p);
     return p;
@@ -263,6 +263,9 @@ __global__ __launch_bounds__(1024) void finalize_loss_kernel(const double* __res
 
 pods_status run_loss(const LossArgs& a) {
     const LossPlan p = plan_loss(a.R, a.T, a.d, a.V, a.dt, a.workspace_bytes);
+    if (p.total > a.workspace_bytes)
+        return fail(PODS_ERR_WORKSPACE, "grpo_token_loss_fwd_bwd: layout needs %zu B, workspace has %zu B", p.total,
+                    a.workspace_bytes);
     unsigned char* ws = a.workspace;
     auto* hdr = reinterpret_cast<LossHeader*>(ws + p.off_hdr);
     auto* offsets = reinterpret_cast<int32_t*>(ws + p.off_offsets);

@@ -61,6 +61,32 @@ def test_loss_argument_checks_and_workspace_query():
     assert lib.grpo_token_loss_workspace_bytes(16, 64, 256, 1024, lib.PODS_F32) > 0
 
 
+@pytest.mark.parametrize("shape", [(2, 64, 4096, 151936), (1, 256, 8192, 128256), (2, 64, 4096, 70000),
+                                   (512, 1024, 2048, 151936), (128, 2048, 3584, 152064), (3, 50, 128, 1000),
+                                   (16, 64, 256, 1024), (1, 1, 64, 40000)])
+def test_workspace_layout_never_exceeds_the_workspace(shape):
+    """For every workspace size from the minimum to beyond the recommendation, the arrays a call lays out
+    end inside the workspace (the layout's size is not monotone in the vocabulary chunk it picks)."""
+    R, T, d, V = shape
+    least = lib.grpo_token_loss_workspace_min_bytes(R, T, d, V, lib.PODS_BF16)
+    rec = lib.grpo_token_loss_workspace_bytes(R, T, d, V, lib.PODS_BF16)
+    assert 0 < least <= rec
+    assert lib.grpo_token_loss_workspace_used_bytes(R, T, d, V, lib.PODS_BF16, least - 1) == 0
+    sizes = {least, least + 256, rec - 256, rec, rec + 256, rec + (64 << 20)}
+    steps = 400
+    sizes.update(least + (rec + (64 << 20) - least) * i // steps for i in range(steps + 1))
+    window = range(max(least, rec - (48 << 20)), rec, 1 << 18)      # fine steps just below the recommendation
+    sizes.update(window)
+    prev_used = 0
+    for b in sorted(sizes):
+        if b < least:
+            continue
+        used = lib.grpo_token_loss_workspace_used_bytes(R, T, d, V, lib.PODS_BF16, b)
+        assert least <= used <= b, (shape, b, used)
+    assert lib.grpo_token_loss_workspace_used_bytes(R, T, d, V, lib.PODS_BF16, rec) == rec
+    assert lib.grpo_token_loss_workspace_used_bytes(R, T, d, V, lib.PODS_BF16, rec + (1 << 30)) == rec
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     from paper_2504_13818_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
