@@ -268,6 +268,26 @@ pods_status grpo_token_loss_fwd_bwd_ex(const void* hidden, const void* w_lm, con
                                        int32_t flags, float* loss, float* logp_out, float* d_hidden,
                                        float* d_w_lm, void* workspace, size_t workspace_bytes, void* stream);
 
+/* grpo_token_loss_fwd_bwd for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): no workspace argument; the working arrays live
+ * in a device array built into the library, PODS_STATIC_WORKSPACE_BYTES per GPU, which every GPU the
+ * library runs on holds until the process ends.  The call allocates and frees nothing.  Sizes whose
+ * minimal workspace (grpo_token_loss_workspace_min_bytes) exceeds that array are rejected with
+ * PODS_ERR_UNSUPPORTED before anything is launched.  Within the array the call picks its vocabulary
+ * chunk as grpo_token_loss_fwd_bwd does for a workspace of that size, so the results are those of that
+ * call.  The array belongs to the GPU that is current when the call is made; all calls on one GPU share
+ * it, so two calls that overlap in time on the same GPU (different streams or threads) race: serialise
+ * them.  Each call writes every part of the array it later reads; nothing is kept between calls.
+ * grpo_token_loss_static_workspace_bytes() returns PODS_STATIC_WORKSPACE_BYTES.  All other arguments as
+ * in grpo_token_loss_fwd_bwd. */
+#define PODS_STATIC_WORKSPACE_BYTES (64u << 20)
+size_t grpo_token_loss_static_workspace_bytes(void);
+pods_status grpo_token_loss_fwd_bwd_static(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                           const float* old_logp, const float* adv, const int32_t* lengths,
+                                           int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
+                                           float clip_eps, float grad_scale, float* loss, float* logp_out,
+                                           float* d_hidden, float* d_w_lm, void* stream);
+
 /* Per-launch timing for benchmarks (not part of the method).  pods_profile_enable(1) makes every
  * later library call on this thread bracket each of its kernel launches with a pair of HIP events
  * on the call's stream, and discards earlier records; pods_profile_enable(0) stops recording.

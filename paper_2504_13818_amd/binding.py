@@ -16,7 +16,8 @@ EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_ad
                     "grpo_token_loss_fwd_bwd_ex",
                     "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_workspace_used_bytes",
-                    "grpo_token_loss_fwd_bwd",
+                    "grpo_token_loss_fwd_bwd", "grpo_token_loss_fwd_bwd_static",
+                    "grpo_token_loss_static_workspace_bytes",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
 
 _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
@@ -67,6 +68,11 @@ def load():
         f.restype = ctypes.c_int
         f.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                       ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.grpo_token_loss_fwd_bwd_static.restype = ctypes.c_int
+    lib.grpo_token_loss_fwd_bwd_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
+                                                   ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp]
+    lib.grpo_token_loss_static_workspace_bytes.restype = _sz
+    lib.grpo_token_loss_static_workspace_bytes.argtypes = []
     lib.grpo_token_loss_fwd_bwd_kl.restype = ctypes.c_int
     lib.grpo_token_loss_fwd_bwd_kl.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                                ctypes.c_int, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp, _vp, _sz,
@@ -328,4 +334,33 @@ def grpo_token_loss_fwd_bwd(hidden, w_lm, tokens, old_logp, adv, lengths, clip_e
         _ptr(out["d_hidden"]), _ptr(out["d_w_lm"]), _ptr(workspace), workspace.numel(),
         _stream(stream)))
     out["workspace"] = workspace
+    return out
+
+
+def grpo_token_loss_static_workspace_bytes() -> int:
+    return int(load().grpo_token_loss_static_workspace_bytes())
+
+
+def grpo_token_loss_fwd_bwd_static(hidden, w_lm, tokens, old_logp, adv, lengths, clip_eps: float,
+                                   grad_scale: float = 1.0, out=None, stream=None):
+    """grpo_token_loss_fwd_bwd on the library's built-in workspace: the call itself allocates nothing, so
+    `out` must carry all four preallocated outputs (loss[1], logp[R, T] or None, d_hidden[R, T, d],
+    d_w_lm[V, d], float32 on the device)."""
+    import torch
+    dt = _dt(hidden)
+    _need(hidden, hidden.dtype, "hidden")
+    _need(w_lm, hidden.dtype, "w_lm")
+    _need(tokens, torch.int32, "tokens")
+    _need(old_logp, torch.float32, "old_logp")
+    _need(adv, torch.float32, "adv")
+    if lengths is not None:
+        _need(lengths, torch.int32, "lengths")
+    if out is None or any(k not in out for k in ("loss", "logp", "d_hidden", "d_w_lm")):
+        raise ValueError("grpo_token_loss_fwd_bwd_static: out must hold loss, logp (or None), d_hidden and d_w_lm")
+    R, T, d = hidden.shape
+    V = w_lm.shape[0]
+    _check(load().grpo_token_loss_fwd_bwd_static(
+        _ptr(hidden), _ptr(w_lm), _ptr(tokens), _ptr(old_logp), _ptr(adv), _ptr(lengths), R, T, d, V, dt,
+        float(clip_eps), float(grad_scale), _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["d_hidden"]),
+        _ptr(out["d_w_lm"]), _stream(stream)))
     return out

@@ -2,6 +2,7 @@
 #include "common.h"
 #include "loss.h"
 
+#include <mutex>
 #include <vector>
 
 namespace pods {
@@ -263,6 +264,60 @@ pods_status grpo_token_loss_fwd_bwd_ex(const void* hidden, const void* w_lm, con
         return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_ex: kl_coef = %g needs ref_logp", (double)kl_coef);
     return token_loss_entry(hidden, w_lm, tokens, old_logp, ref_logp, kl_coef, adv, lengths, R, T, d, V, dt, clip_eps,
                             grad_scale, loss, logp_out, d_hidden, d_w_lm, flags, workspace, workspace_bytes, stream);
+}
+
+// ---- grpo_token_loss_fwd_bwd_static: the workspace is a device array of this library -----------------
+namespace {
+constexpr size_t kScratchBytes = (size_t)PODS_STATIC_WORKSPACE_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace
+// One copy per GPU, at that GPU's own address; in host code the name is only a handle for
+// hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU, looked up once
+
+pods_status scratch_on_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(PODS_ERR_RUNTIME, "grpo_token_loss_fwd_bwd_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(PODS_ERR_UNSUPPORTED, "grpo_token_loss_fwd_bwd_static: device %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr)
+            return fail(PODS_ERR_RUNTIME, "grpo_token_loss_fwd_bwd_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PODS_OK;
+}
+}  // namespace
+
+size_t grpo_token_loss_static_workspace_bytes(void) { return kScratchBytes; }
+
+pods_status grpo_token_loss_fwd_bwd_static(const void* hidden, const void* w_lm, const int32_t* tokens,
+                                           const float* old_logp, const float* adv, const int32_t* lengths,
+                                           int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
+                                           float clip_eps, float grad_scale, float* loss, float* logp_out,
+                                           float* d_hidden, float* d_w_lm, void* stream) {
+    if (!loss_sizes_ok(R, T, d, V, dt))
+        return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_fwd_bwd_static: R=%d T=%d d=%d V=%d dtype=%d invalid", R, T, d,
+                    V, (int)dt);
+    const size_t need = plan_loss(R, T, d, V, dt, 1).total;
+    if (need > kScratchBytes)
+        return fail(PODS_ERR_UNSUPPORTED,
+                    "grpo_token_loss_fwd_bwd_static: these sizes need %zu B of workspace, the built-in one has %zu B; "
+                    "use grpo_token_loss_fwd_bwd with a workspace of the caller's",
+                    need, kScratchBytes);
+    void* ws = nullptr;
+    pods_status st = scratch_on_current_device(&ws);
+    if (st != PODS_OK) return st;
+    return token_loss_entry(hidden, w_lm, tokens, old_logp, nullptr, 0.0f, adv, lengths, R, T, d, V, dt, clip_eps,
+                            grad_scale, loss, logp_out, d_hidden, d_w_lm, 0, ws, kScratchBytes, stream);
 }
 
 pods_status pods_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,

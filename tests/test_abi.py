@@ -87,6 +87,21 @@ def test_workspace_layout_never_exceeds_the_workspace(shape):
     assert lib.grpo_token_loss_workspace_used_bytes(R, T, d, V, lib.PODS_BF16, rec + (1 << 30)) == rec
 
 
+def test_static_workspace_entry_checks_sizes_on_the_host():
+    """The entry point without a workspace argument rejects, before touching any device, sizes whose
+    minimal workspace exceeds its built-in array."""
+    l = lib.load()
+    one = ctypes.c_void_p(256)
+    size = lib.grpo_token_loss_static_workspace_bytes()
+    assert size == 64 << 20
+    assert lib.grpo_token_loss_workspace_min_bytes(512, 1024, 2048, 151936, lib.PODS_BF16) > size
+    st = l.grpo_token_loss_fwd_bwd_static(one, one, one, one, one, None, 512, 1024, 2048, 151936, lib.PODS_BF16,
+                                          0.2, 1.0, one, None, one, one, None)
+    assert st == 2 and "built-in" in lib.pods_last_error()
+    assert l.grpo_token_loss_fwd_bwd_static(one, one, one, one, one, None, 0, 8, 64, 100, lib.PODS_BF16,
+                                            0.2, 1.0, one, None, one, one, None) == 1
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     from paper_2504_13818_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
