@@ -25,13 +25,19 @@
  *   - Every pointer is a DEVICE pointer unless marked "host".  `stream` is a hipStream_t passed
  *     as void* (NULL = the default stream).  Calls only enqueue work on `stream`: no host
  *     synchronisation, no host read of device data, no device allocation.
- *   - The caller owns every buffer, including the workspace.  Outputs are overwritten, inputs
- *     are never modified.  Arrays are dense, row-major, 0-based indices (the paper is 1-based).
+ *   - The caller owns every buffer, including the workspace.  The library keeps no device memory
+ *     and no state between calls, with two stated exceptions: the built-in working array of
+ *     grpo_token_loss_fwd_bwd_static, and the benchmark hooks of pods_profile.h.  Outputs are
+ *     overwritten, inputs are never modified.  Arrays are dense, row-major, 0-based indices (the paper is 1-based).
  *   - The return value is a pods_status; nothing throws or aborts across this boundary.
  *     Conditions the host can see (null pointers, non-positive sizes, m > n, a workspace that
  *     is too small, a shape no kernel variant covers) are reported before anything is launched.
- *     Conditions that live in device data (NaN or infinite rewards, a token id outside [0, V),
- *     a length outside [0, T]) are not checked and give undefined results.
+ *     Conditions that live in device data cannot be reported by a call that never waits for the
+ *     device.  The token loss takes a length outside [0, T] and a token id outside [0, V) as
+ *     clamped to the nearest valid value, so that nothing is read or written out of bounds, and
+ *     counts them in its report (grpo_token_loss_report); its results are then meaningless.  NaN or
+ *     infinite rewards give undefined selections and advantages (but no out-of-bounds access);
+ *     pods_check_rewards is the optional launch that finds them.
  *   - pods_last_error() returns a host string describing the last failure on this thread.
  */
 #ifndef PODS_H_
@@ -72,6 +78,16 @@ typedef enum { PODS_F32 = 0, PODS_BF16 = 1 } pods_dtype;
  */
 pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m,
                         int32_t* sel_idx, int32_t* sel_k, void* stream);
+
+/* Optional argument check for the calls above and below that read rewards: counts the rewards that are
+ * NaN or infinite, which Sec. 3.2's rules and advantages define nothing for.  One extra launch on
+ * `stream`; the caller reads the report when it next synchronises.
+ *
+ *   rewards  [B, n] float32, in
+ *   report   [2] int32, out (device): report[0] = number of non-finite rewards, report[1] = flat
+ *            index b*n + i of the first one, or -1.  B*n < 2^31.
+ */
+pods_status pods_check_rewards(const float* rewards, int32_t B, int32_t n, int32_t* report, void* stream);
 
 /* The down-sampling step of the PODS framework (Algorithm 1, step 3) under a chosen rule
  * (Sec. 3.2 for the first three, Sec. 3.3 for max-variance).  All rules read positions of the
@@ -205,8 +221,10 @@ size_t grpo_token_loss_workspace_used_bytes(int32_t R, int32_t T, int32_t d, int
  *
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; softmax statistics are
  * fp32.  For the two gradient contractions the softmax part of the per-logit gradient is rounded
- * to fp16 (scaled so that it cannot overflow) and the generated token's own logit is applied in
- * fp32; results are deterministic (no floating-point atomics).  A bf16 call with d not a multiple
+ * to fp16 (scaled so that it cannot overflow), the weight and the token-weighted hidden state are
+ * copied to fp16 under power-of-two scales taken from their largest magnitudes (exact for elements
+ * within 2^22 of the largest, see pods_loss_report), and the generated token's own logit is applied
+ * in fp32; results are deterministic (no floating-point atomics).  A bf16 call with d not a multiple
  * of 64, and every fp32 call, uses plain fp32 vector arithmetic throughout.  d <= 16384, R*T <= 2^30,
  * T <= 16776960 (PODS_ERR_UNSUPPORTED beyond).
  */
@@ -268,6 +286,40 @@ pods_status grpo_token_loss_fwd_bwd_ex(const void* hidden, const void* w_lm, con
                                        int32_t flags, float* loss, float* logp_out, float* d_hidden,
                                        float* d_w_lm, void* workspace, size_t workspace_bytes, void* stream);
 
+/* What a token-loss call (any of the entry points above and below) found in its device-side arguments,
+ * and its diagnostic counters; kept in the first 64 bytes of the workspace after the call.
+ *
+ *   valid_tokens      N = sum of the lengths (after clamping to [0, T])
+ *   backward_tokens   valid tokens the backward pass covered (N unless zero-advantage rollouts were skipped)
+ *   clipped_tokens    valid tokens at which the clipped term of the surrogate is the selected one, so no
+ *                     gradient flows: (a > 0 and rho > 1+eps) or (a < 0 and rho < 1-eps).  Divided by
+ *                     valid_tokens this is the clip fraction.
+ *   bad_lengths       rollouts whose length lay outside [0, T];  bad_tokens: valid positions whose token
+ *                     id lay outside [0, V).  Both were taken as clamped; non-zero means the results of
+ *                     the call are meaningless.
+ *   max_abs_g         max over valid tokens of |d loss / d log pi(y)| (times grad_scale)
+ *   max_abs_w, max_abs_hidden   largest |w_lm| element and largest |hidden| element over valid positions
+ *                     (bf16 matrix-core path only, 0 otherwise).  A NaN or infinity here means the inputs
+ *                     held one.  The two fp16 operands of the gradient contractions are scaled by powers
+ *                     of two chosen from these maxima, so no finite bf16 input overflows them; elements
+ *                     more than 2^22 below the maximum lose low-order bits (fp16 subnormals).
+ *
+ * grpo_token_loss_report copies the report to HOST memory: it waits for `stream` (the only token-loss call
+ * that synchronises with the device).  workspace = the workspace of the call to report on, or NULL for
+ * the built-in one of grpo_token_loss_fwd_bwd_static on the current GPU. */
+typedef struct {
+    int32_t valid_tokens;
+    int32_t backward_tokens;
+    int32_t clipped_tokens;
+    int32_t bad_lengths;
+    int32_t bad_tokens;
+    float max_abs_g;
+    float max_abs_w;
+    float max_abs_hidden;
+    int32_t reserved[8];
+} pods_loss_report;
+pods_status grpo_token_loss_report(const void* workspace, pods_loss_report* report /* host */, void* stream);
+
 /* grpo_token_loss_fwd_bwd for callers that cannot allocate device memory (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): no workspace argument; the working arrays live
  * in a device array built into the library, PODS_STATIC_WORKSPACE_BYTES per GPU, which every GPU the
@@ -287,16 +339,6 @@ pods_status grpo_token_loss_fwd_bwd_static(const void* hidden, const void* w_lm,
                                            int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt,
                                            float clip_eps, float grad_scale, float* loss, float* logp_out,
                                            float* d_hidden, float* d_w_lm, void* stream);
-
-/* Per-launch timing for benchmarks (not part of the method).  pods_profile_enable(1) makes every
- * later library call on this thread bracket each of its kernel launches with a pair of HIP events
- * on the call's stream, and discards earlier records; pods_profile_enable(0) stops recording.
- * pods_profile_count() is the number of launches recorded so far; pods_profile_get(i, ...) waits for
- * launch i to finish (the only call here that synchronises with the device) and returns the
- * kernel's name (a static host string) and its duration in milliseconds. */
-pods_status pods_profile_enable(int32_t enable);
-int32_t pods_profile_count(void);
-pods_status pods_profile_get(int32_t i, const char** name, float* ms);
 
 /* Host string for the last error on the calling thread; valid until the next failing call. */
 const char* pods_last_error(void);

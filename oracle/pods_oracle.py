@@ -268,7 +268,7 @@ def token_rows(h: np.ndarray, w: np.ndarray, y: np.ndarray, old_logp: np.ndarray
     dz = -g[:, None] * p
     dz[rows, y] += g
     d_h = (dz.astype(gemm_dtype, copy=False) @ wg).astype(np.float64)
-    return dict(logp=logp, obj=obj, g=g, dz=dz, d_h=d_h, lse=lse)
+    return dict(logp=logp, obj=obj, g=g, dz=dz, d_h=d_h, lse=lse, inactive=inactive, rho=rho)
 
 
 def grpo_token_loss(hidden: np.ndarray, w: np.ndarray, tokens: np.ndarray, old_logp: np.ndarray,
@@ -281,7 +281,8 @@ def grpo_token_loss(hidden: np.ndarray, w: np.ndarray, tokens: np.ndarray, old_l
     hidden[R, T, d], w[V, d], tokens[R, T], old_logp[R, T], adv[R], lengths[R] (None: all T).
     Returns dict(loss, logp[R, T], d_hidden[R, T, d], d_w[V, d]); float64.  Positions at or past
     a rollout's length get logp = 0 and a zero d_hidden row.  The gradients are those of
-    grad_scale * loss.
+    grad_scale * loss.  Also returned: clipped[R, T] (bool), the valid positions where the clipped
+    term is the selected one so that no gradient flows, and rho[R, T], the importance ratios there.
     """
     R, T, d = hidden.shape
     V = w.shape[0]
@@ -296,6 +297,8 @@ def grpo_token_loss(hidden: np.ndarray, w: np.ndarray, tokens: np.ndarray, old_l
     logp = np.zeros((R, T))
     d_hidden = np.zeros((R, T, d))
     d_w = np.zeros((V, d)) if want_dw else None
+    clipped = np.zeros((R, T), dtype=bool)
+    rho = np.zeros((R, T))
     for s in range(0, len(ii), block):
         bi, bt = ii[s:s + block], tt[s:s + block]
         hb = hidden[bi, bt]
@@ -305,6 +308,8 @@ def grpo_token_loss(hidden: np.ndarray, w: np.ndarray, tokens: np.ndarray, old_l
         loss -= float((cb * out["obj"]).sum())
         logp[bi, bt] = out["logp"]
         d_hidden[bi, bt] = out["d_h"]
+        clipped[bi, bt] = out["inactive"]
+        rho[bi, bt] = out["rho"]
         if want_dw:
             d_w += (out["dz"].astype(gemm_dtype, copy=False).T @ hb.astype(gemm_dtype, copy=False)).astype(np.float64)
-    return dict(loss=loss, logp=logp, d_hidden=d_hidden, d_w=d_w)
+    return dict(loss=loss, logp=logp, d_hidden=d_hidden, d_w=d_w, clipped=clipped, rho=rho)

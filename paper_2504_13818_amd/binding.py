@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_ad
                     "grpo_token_loss_workspace_bytes",
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_workspace_used_bytes",
                     "grpo_token_loss_fwd_bwd", "grpo_token_loss_fwd_bwd_static",
-                    "grpo_token_loss_static_workspace_bytes",
+                    "grpo_token_loss_static_workspace_bytes", "grpo_token_loss_report", "pods_check_rewards",
                     "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
 
 _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
@@ -26,6 +26,14 @@ _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c
 class PodsRecord(ctypes.Structure):
     """pods_record of include/pods.h."""
     _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("row_bytes", ctypes.c_size_t)]
+
+
+class PodsLossReport(ctypes.Structure):
+    """pods_loss_report of include/pods.h."""
+    _fields_ = [("valid_tokens", ctypes.c_int32), ("backward_tokens", ctypes.c_int32),
+                ("clipped_tokens", ctypes.c_int32), ("bad_lengths", ctypes.c_int32), ("bad_tokens", ctypes.c_int32),
+                ("max_abs_g", ctypes.c_float), ("max_abs_w", ctypes.c_float), ("max_abs_hidden", ctypes.c_float),
+                ("reserved", ctypes.c_int32 * 8)]
 
 
 class PodsError(RuntimeError):
@@ -73,6 +81,10 @@ def load():
                                                    ctypes.c_int, _f32, _f32, _vp, _vp, _vp, _vp, _vp]
     lib.grpo_token_loss_static_workspace_bytes.restype = _sz
     lib.grpo_token_loss_static_workspace_bytes.argtypes = []
+    lib.grpo_token_loss_report.restype = ctypes.c_int
+    lib.grpo_token_loss_report.argtypes = [_vp, ctypes.POINTER(PodsLossReport), _vp]
+    lib.pods_check_rewards.restype = ctypes.c_int
+    lib.pods_check_rewards.argtypes = [_vp, _i32, _i32, _vp, _vp]
     lib.grpo_token_loss_fwd_bwd_kl.restype = ctypes.c_int
     lib.grpo_token_loss_fwd_bwd_kl.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32,
                                                ctypes.c_int, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp, _vp, _sz,
@@ -364,3 +376,23 @@ def grpo_token_loss_fwd_bwd_static(hidden, w_lm, tokens, old_logp, adv, lengths,
         float(clip_eps), float(grad_scale), _ptr(out["loss"]), _ptr(out["logp"]), _ptr(out["d_hidden"]),
         _ptr(out["d_w_lm"]), _stream(stream)))
     return out
+
+
+def grpo_token_loss_report(workspace=None, stream=None) -> dict:
+    """The report of the last token-loss call on `workspace` (a uint8 CUDA tensor; None = the built-in
+    workspace of grpo_token_loss_fwd_bwd_static) as a dict.  Waits for the stream."""
+    rep = PodsLossReport()
+    _check(load().grpo_token_loss_report(_ptr(workspace), ctypes.byref(rep), _stream(stream)))
+    return {name: getattr(rep, name) for name, _ in PodsLossReport._fields_ if name != "reserved"}
+
+
+def pods_check_rewards(rewards, report=None, stream=None):
+    """rewards[B, n] float32 (device) -> report[2] int32 (device): number of non-finite rewards and the
+    flat index of the first one (-1 if none)."""
+    import torch
+    _need(rewards, torch.float32, "rewards")
+    B, n = rewards.shape
+    if report is None:
+        report = torch.empty((2,), dtype=torch.int32, device=rewards.device)
+    _check(load().pods_check_rewards(_ptr(rewards), B, n, _ptr(report), _stream(stream)))
+    return report

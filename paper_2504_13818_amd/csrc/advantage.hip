@@ -80,6 +80,28 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const W* __restrict__ 
     }
 }
 
+// Optional argument check for the selection step: rewards that are NaN or infinite (for which the
+// down-sampling rules define nothing) are counted, and the flat index of the first one is kept.
+__global__ void check_rewards_init_kernel(int32_t* __restrict__ report) {
+    report[0] = 0;
+    report[1] = -1;
+}
+__global__ __launch_bounds__(256) void check_rewards_kernel(const float* __restrict__ rewards, int64_t count,
+                                                            int32_t* __restrict__ report) {
+    int bad = 0;
+    uint32_t first = 0xFFFFFFFFu;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+        if ((__float_as_uint(rewards[i]) & 0x7F800000u) == 0x7F800000u) {
+            ++bad;
+            first = min(first, (uint32_t)i);
+        }
+    }
+    if (bad != 0) {   // integer count and minimum: order-independent
+        atomicAdd(&report[0], bad);
+        atomicMin(reinterpret_cast<uint32_t*>(&report[1]), first);   // -1 reads as the largest unsigned
+    }
+}
+
 template <typename W>
 void launch_gather_width(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,
                          size_t row_bytes, void* dst, hipStream_t stream) {
@@ -100,6 +122,16 @@ pods_status launch_gather_rows(const void* src, const int32_t* sel_idx, int32_t 
     else if ((bits & 3) == 0) launch_gather_width<uint32_t>(src, sel_idx, B, n, m, row_bytes, dst, stream);
     else launch_gather_width<uint8_t>(src, sel_idx, B, n, m, row_bytes, dst, stream);
     return check_launch("pods_gather_rows");
+}
+
+pods_status launch_check_rewards(const float* rewards, int64_t count, int32_t* report, hipStream_t stream) {
+    PODS_LAUNCH("pods_check_rewards (init)", stream, check_rewards_init_kernel, dim3(1), dim3(1), 0, stream, report);
+    pods_status st = check_launch("pods_check_rewards (init)");
+    if (st != PODS_OK) return st;
+    const unsigned grid = (unsigned)(ceil_div(count, 256) < 2048 ? ceil_div(count, 256) : 2048);
+    PODS_LAUNCH("pods_check_rewards", stream, check_rewards_kernel, dim3(grid), dim3(256), 0, stream, rewards, count,
+                report);
+    return check_launch("pods_check_rewards");
 }
 
 pods_status launch_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,

@@ -1,6 +1,7 @@
 // C ABI of the PODS HIP library: argument checks, then dispatch to the kernel families.
 #include "common.h"
 #include "loss.h"
+#include "pods_profile.h"
 
 #include <mutex>
 #include <vector>
@@ -57,6 +58,13 @@ pods_status pods_profile_enable(int32_t enable) {
     auto& p = profile();
     p.enabled = enable != 0;
     p.used = 0;
+    if (!p.enabled) {   // switched off: the events go too
+        for (Stage& s : p.stages) {
+            (void)hipEventDestroy(s.start);
+            (void)hipEventDestroy(s.stop);
+        }
+        p.stages.clear();
+    }
     return PODS_OK;
 }
 
@@ -83,6 +91,15 @@ pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m, i
     if (n > 4096) return fail(PODS_ERR_UNSUPPORTED, "pods_select: n=%d exceeds 4096", n);
     return launch_select(rewards, nullptr, B, n, m, PODS_RULE_MAXVAR, sel_idx, sel_k,
                          static_cast<hipStream_t>(stream));
+}
+
+pods_status pods_check_rewards(const float* rewards, int32_t B, int32_t n, int32_t* report, void* stream) {
+    if (rewards == nullptr || report == nullptr)
+        return fail(PODS_ERR_INVALID_ARG, "pods_check_rewards: rewards and report must not be null");
+    if (B <= 0 || n <= 0) return fail(PODS_ERR_INVALID_ARG, "pods_check_rewards: B=%d n=%d must be positive", B, n);
+    if ((int64_t)B * n > (int64_t)0x7fffffff)
+        return fail(PODS_ERR_UNSUPPORTED, "pods_check_rewards: more than 2^31 - 1 rewards");
+    return launch_check_rewards(rewards, (int64_t)B * n, report, static_cast<hipStream_t>(stream));
 }
 
 pods_status pods_downsample(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n,
@@ -298,6 +315,22 @@ pods_status scratch_on_current_device(void** out) {
 }  // namespace
 
 size_t grpo_token_loss_static_workspace_bytes(void) { return kScratchBytes; }
+
+pods_status grpo_token_loss_report(const void* workspace, pods_loss_report* report, void* stream) {
+    if (report == nullptr) return fail(PODS_ERR_INVALID_ARG, "grpo_token_loss_report: report must not be null");
+    const void* src = workspace;
+    if (src == nullptr) {   // the built-in working array of grpo_token_loss_fwd_bwd_static
+        void* ws = nullptr;
+        pods_status st = scratch_on_current_device(&ws);
+        if (st != PODS_OK) return st;
+        src = ws;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(report, src, sizeof(pods_loss_report), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(PODS_ERR_RUNTIME, "grpo_token_loss_report: %s", hipGetErrorString(e));
+    return PODS_OK;
+}
 
 pods_status grpo_token_loss_fwd_bwd_static(const void* hidden, const void* w_lm, const int32_t* tokens,
                                            const float* old_logp, const float* adv, const int32_t* lengths,

@@ -56,6 +56,7 @@ pods_status launch_select(const float* rewards, const uint32_t* rand_keys, int32
                           int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream);
 pods_status launch_advantage(const float* rewards, const int32_t* sel_idx, int32_t B, int32_t n,
                              int32_t m, float std_eps, bool stats_from_all, float* adv, hipStream_t stream);
+pods_status launch_check_rewards(const float* rewards, int64_t count, int32_t* report, hipStream_t stream);
 pods_status launch_gather_rows(const void* src, const int32_t* sel_idx, int32_t B, int32_t n, int32_t m,
                                size_t row_bytes, void* dst, hipStream_t stream);
 pods_status launch_downsample_gather(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,

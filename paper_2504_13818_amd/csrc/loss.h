@@ -34,26 +34,56 @@ struct LossArgs {
     hipStream_t stream;
 };
 
-// Device header at the start of the workspace.
+// Device header at the start of the workspace.  Its first 64 bytes are the public pods_loss_report.
 struct LossHeader {
-    int32_t n_valid;     // N
-    uint32_t gmax_bits;  // bit pattern of max_t |g_t| (non-negative floats order as integers)
-    int32_t n_bwd;       // packed rows the backward pass covers: N, or only the rows of rollouts with
-                         // a non-zero advantage (they are packed first when those are skipped)
-    int32_t pad[61];
+    int32_t n_valid;       // N
+    int32_t n_bwd;         // packed rows the backward pass covers: N, or only the rows of rollouts with
+                           // a non-zero advantage (they are packed first when those are skipped)
+    int32_t clipped;       // valid tokens whose clipped term is the selected one (no gradient)
+    int32_t bad_lengths;   // rollouts whose length lay outside [0, T] (taken as clamped)
+    int32_t bad_tokens;    // valid positions whose token id lay outside [0, V) (taken as clamped)
+    uint32_t gmax_bits;    // bit patterns of max_t |g_t|, max |W_lm|, max |h| over valid rows
+    uint32_t wmax_bits;    // (non-negative floats order as integers; the last two on the bf16
+    uint32_t hmax_bits;    //  matrix-core path only)
+    int32_t pad[56];
 };
+static_assert(sizeof(LossHeader) == 256, "the header is one 256-byte slot of the workspace");
+static_assert(sizeof(pods_loss_report) == 64, "the report is the head of the header");
 
-// Scale 2^-floor(log2 gmax) that brings the per-token weights g_t into [0, 2).
-__device__ __forceinline__ float g_range_scale(const LossHeader* hdr) {
-    const uint32_t e = (hdr->gmax_bits >> 23) & 0xFFu;
-    if (hdr->gmax_bits == 0u) return 1.0f;
-    const uint32_t se = e == 0u ? 253u : (e >= 253u ? 1u : 254u - e);
-    return __uint_as_float(se << 23);
+// Valid prefix length of rollout i: lengths[i] clamped to [0, T] (T when lengths is null).
+__device__ __forceinline__ int rollout_len(const int32_t* lengths, int i, int T) {
+    if (lengths == nullptr) return T;
+    const int len = lengths[i];
+    return len < 0 ? 0 : (len > T ? T : len);
 }
 
-// Fixed power-of-two scales of the fp16 operands of the two gradient contractions.
+// 2^(target - floor(log2 x)) for the float with bit pattern `bits` (x >= 0): brings x into
+// [2^target, 2^(target+1)).  1 for x = 0; the exponent of the result is kept inside [-100, 100], and a
+// non-finite x is treated as the largest finite binade.
+__device__ __forceinline__ int float_exponent(uint32_t bits) {
+    const int e = (int)((bits >> 23) & 0xFFu);
+    return (e == 0 ? 1 : (e == 255 ? 254 : e)) - 127;
+}
+__device__ __forceinline__ float pow2(int e) {
+    e = e < -100 ? -100 : (e > 100 ? 100 : e);
+    return __uint_as_float((uint32_t)(e + 127) << 23);
+}
+
+// Power-of-two range scales of the two fp16 gradient operands (exact for bf16 data that stays in fp16's
+// normal range, i.e. within 2^-22 of the largest element):
+//   W16 = fp16(s_w W),  s_w brings max |W| into [2^8, 2^9)
+//   H16 = fp16(s_h g_t h_t),  s_h brings (max |g|) (max |h|) below 2^14 (and at least to 2^12)
+__device__ __forceinline__ float w_range_scale(const LossHeader* hdr) {
+    if (hdr->wmax_bits == 0u) return 1.0f;
+    return pow2(8 - float_exponent(hdr->wmax_bits));
+}
+__device__ __forceinline__ float g_range_scale(const LossHeader* hdr) {
+    if (hdr->gmax_bits == 0u || hdr->hmax_bits == 0u) return 1.0f;
+    return pow2(12 - float_exponent(hdr->gmax_bits) - float_exponent(hdr->hmax_bits));
+}
+
+// Fixed power-of-two scale of the fp16 softmax operand of the two gradient contractions.
 constexpr float kQScale = 16384.0f;  // q = kQScale softmax (0 at v = y): 0 <= q <= 2^14
-constexpr float kWScale = 256.0f;    // the fp16 weight copy of the gradient contractions holds kWScale * W
 
 constexpr int kTile = 256;          // token / vocab / hidden tile edge of the matrix-core kernels
 constexpr int kDefaultVocabChunk = 8192;

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t* __res
             const int i = base + tid;
             const bool mine = i < R && (!skip || ((adv[i] != 0.0f) == (pass == 0)));
             int32_t len = 0;
-            if (mine) len = lengths ? lengths[i] : T;
+            if (mine) len = rollout_len(lengths, i, T);
             int32_t x = len;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
@@ -135,26 +135,40 @@ __global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t* __res
         offsets[R] = carry;
         hdr->n_valid = carry;
         hdr->n_bwd = skip ? n_live : carry;
+        hdr->clipped = 0;
+        hdr->bad_lengths = 0;
+        hdr->bad_tokens = 0;
         hdr->gmax_bits = 0u;
+        hdr->wmax_bits = 0u;
+        hdr->hmax_bits = 0u;
     }
 }
 
-// Packed row -> flat position map and packed token ids; clears logp_out at padded positions.
-__global__ __launch_bounds__(256) void fill_rows_kernel(const int32_t* __restrict__ lengths,
+// Packed row -> flat position map and packed token ids; clears logp_out at padded positions.  Lengths
+// outside [0, T] and token ids outside [0, V) are taken as clamped (nothing downstream can then index out
+// of bounds) and counted in the header.
+__global__ __launch_bounds__(256) void fill_rows_kernel(LossHeader* __restrict__ hdr,
+                                                        const int32_t* __restrict__ lengths,
                                                         const int32_t* __restrict__ tokens,
-                                                        const int32_t* __restrict__ offsets, int T,
+                                                        const int32_t* __restrict__ offsets, int T, int V,
                                                         int32_t* __restrict__ row_map,
                                                         int32_t* __restrict__ tok,
                                                         float* __restrict__ logp_out) {
     const int i = blockIdx.x;                       // rollouts ride on grid.x (no 65535 limit)
     const int t = blockIdx.y * 256 + threadIdx.x;
+    if (t == 0 && lengths != nullptr && (lengths[i] < 0 || lengths[i] > T)) atomicAdd(&hdr->bad_lengths, 1);
     if (t >= T) return;
-    const int len = lengths ? lengths[i] : T;
+    const int len = rollout_len(lengths, i, T);
     const int64_t flat = (int64_t)i * T + t;
     if (t < len) {
         const int p = offsets[i] + t;
         row_map[p] = (int32_t)flat;
-        tok[p] = tokens[flat];
+        int y = tokens[flat];
+        if ((unsigned)y >= (unsigned)V) {
+            atomicAdd(&hdr->bad_tokens, 1);         // an integer count: order-independent
+            y = y < 0 ? 0 : V - 1;
+        }
+        tok[p] = y;
     } else if (logp_out != nullptr) {
         logp_out[flat] = 0.0f;
     }
@@ -167,7 +181,7 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
                                                             float* __restrict__ d_hidden) {
     const int64_t flat = blockIdx.x;
     const int i = (int)(flat / T), t = (int)(flat % T);
-    const int len = lengths ? lengths[i] : T;
+    const int len = rollout_len(lengths, i, T);
     if (t < len && !(skip && adv[i] == 0.0f)) return;
     float* row = d_hidden + flat * d;
     if ((d & 3) == 0) {
@@ -192,10 +206,12 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
     float* __restrict__ logp_out, double* __restrict__ loss_part) {
     __shared__ double red[4];
     __shared__ float redg[4];
+    __shared__ int redc[4];
     const int n_valid = hdr->n_valid;
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     double contrib = 0.0;
     float gabs = 0.0f;
+    bool cut = false;
     if (p < n_valid) {
         float M = -__builtin_huge_valf();
         for (int s = 0; s < slots; ++s) M = fmaxf(M, pmax[s * slot_stride + p]);
@@ -207,7 +223,7 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
         const float lse = M + logf(L);
         const int flat = row_map[p];
         const int i = flat / T;
-        const int len = lengths ? lengths[i] : T;
+        const int len = rollout_len(lengths, i, T);
         const float a = adv[i];
         const float c = 1.0f / ((float)R * (float)len);
         const float logp = zy[p] - lse;
@@ -215,6 +231,7 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
         const float lo = 1.0f - clip_eps, hi = 1.0f + clip_eps;
         float obj = fminf(rho * a, fminf(fmaxf(rho, lo), hi) * a);
         const bool inactive = (a > 0.0f && rho > hi) || (a < 0.0f && rho < lo);
+        cut = inactive;
         float dobj = inactive ? 0.0f : a * rho;   // d obj / d logp
         if (ref_logp != nullptr) {
             // KL penalty, per token: exp(x) - x - 1 with x = log pi_ref(y) - log pi_theta(y)
@@ -236,10 +253,17 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
         contrib += __shfl_xor(contrib, off, 64);
         gabs = fmaxf(gabs, __shfl_xor(gabs, off, 64));
     }
-    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = contrib; redg[threadIdx.x >> 6] = gabs; }
+    const int ncut = __popcll(__ballot(cut));
+    if ((threadIdx.x & 63) == 0) {
+        red[threadIdx.x >> 6] = contrib;
+        redg[threadIdx.x >> 6] = gabs;
+        redc[threadIdx.x >> 6] = ncut;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         loss_part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+        const int nc = redc[0] + redc[1] + redc[2] + redc[3];
+        if (nc > 0) atomicAdd(&hdr->clipped, nc);   // an integer count: order-independent
         const float gm = fmaxf(fmaxf(redg[0], redg[1]), fmaxf(redg[2], redg[3]));
         if (gm > 0.0f) atomicMax(&hdr->gmax_bits, __float_as_uint(gm));  // a max: order-independent
     }
@@ -284,7 +308,7 @@ pods_status run_loss(const LossArgs& a) {
                        a.skip_zero_adv ? 1 : 0, a.R, a.T, offsets, hdr);
     if ((st = check_launch("scan_lengths")) != PODS_OK) return st;
     PODS_LAUNCH("fill_rows", a.stream, fill_rows_kernel, dim3((unsigned)a.R, (unsigned)ceil_div(a.T, 256)), dim3(256),
-                       0, a.stream, a.lengths, a.tokens, offsets, a.T, row_map, tok, a.logp_out);
+                       0, a.stream, hdr, a.lengths, a.tokens, offsets, a.T, a.V, row_map, tok, a.logp_out);
     if ((st = check_launch("fill_rows")) != PODS_OK) return st;
     if (a.lengths != nullptr || a.skip_zero_adv) {
         PODS_LAUNCH("zero_pad_rows", a.stream, zero_pad_rows_kernel, dim3((unsigned)p.ncap), dim3(256), 0, a.stream,

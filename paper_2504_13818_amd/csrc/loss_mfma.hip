@@ -35,6 +35,7 @@
 // Workgroup ids are mapped to tiles so that the 32 workgroups resident on one XCD (one L2) form a
 // 4 x 8 block of tiles and share operand rows.
 #include "loss.h"
+#include "tile_map.h"
 
 namespace pods {
 namespace {
@@ -57,8 +58,6 @@ constexpr int kRecomputeLdsBytes = kTile * kQPitch > kLdsBytes ? kTile * kQPitch
 constexpr int kHPitch = 4 * kTile + 16;            // bytes per token row of the d_hidden half-tile staged in LDS
 constexpr int kDhLdsBytes = 128 * kHPitch > kLdsBytes ? 128 * kHPitch : kLdsBytes;   // 130 KiB
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kXcds = 8;
-constexpr int kSuper0 = 4, kSuper1 = 8;            // tiles per XCD block along the two tile axes (at most)
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
@@ -329,53 +328,6 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
 }
 
-// Workgroup id -> tile (t0, t1) of an n0 x n1 tile grid, so that ids congruent mod 8 (one XCD)
-// walk blocks of 4 x s1 tiles (the 32 workgroups resident on an XCD then share operand rows in its L2).  s1 divides the second axis as evenly as blocks of at most 8 can
-// (14 tiles -> 7 + 7, not 8 + 6): with an even number of unequal block columns the short column would
-// always fall to the same XCDs, which then run out of work early.  Returns false for ids that fall
-// outside the grid.
-__host__ __device__ inline int64_t super_width(int64_t n1) {
-    const int64_t cols = (n1 + kSuper1 - 1) / kSuper1;
-    return (n1 + cols - 1) / cols;
-}
-// The caller of decode_tile passes exactly the n0, n1 the launch was sized with (super_grid_blocks): the
-// mapping of a launch with few blocks depends on both.
-// Blocks go round the XCDs (block b to XCD b mod 8), which keeps the XCDs on neighbouring blocks at any
-// time.  A launch with few blocks (d_w_lm: one or two rounds of long tiles) would leave the XCDs
-// unevenly loaded that way, so there each XCD takes one contiguous eighth of the slots (tiles, and the
-// holes of partial blocks) in block order instead: balanced to within one tile.
-constexpr int64_t kFewBlocks = 64;
-__host__ __device__ inline int64_t super_blocks(int64_t n0, int64_t n1) {
-    const int64_t s1 = super_width(n1);
-    return ((n0 + kSuper0 - 1) / kSuper0) * ((n1 + s1 - 1) / s1);
-}
-__host__ __device__ inline int64_t super_grid_blocks(int64_t n0, int64_t n1) {
-    const int64_t nst = super_blocks(n0, n1), per_block = kSuper0 * super_width(n1);
-    if (nst < kFewBlocks) return (nst * per_block + kXcds - 1) / kXcds * kXcds;
-    return (nst + kXcds - 1) / kXcds * kXcds * per_block;
-}
-__device__ __forceinline__ bool decode_tile(int64_t bid, int64_t n0, int64_t n1, int64_t& t0, int64_t& t1) {
-    const int64_t s1 = super_width(n1);
-    const int64_t per_block = kSuper0 * s1;
-    const int64_t nst1 = (n1 + s1 - 1) / s1;
-    const int64_t nst = super_blocks(n0, n1);
-    const int64_t xcd = bid % kXcds, q = bid / kXcds;   // workgroup ids go round the XCDs
-    int64_t st;
-    int w;
-    if (nst < kFewBlocks) {
-        const int64_t per_xcd = (nst * per_block + kXcds - 1) / kXcds;
-        const int64_t seq = xcd * per_xcd + q;
-        st = seq / per_block;
-        w = (int)(seq % per_block);
-    } else {
-        st = (q / per_block) * kXcds + xcd;
-        w = (int)(q % per_block);
-    }
-    t0 = (st / nst1) * kSuper0 + w / s1;
-    t1 = (st % nst1) * s1 + w % s1;
-    return st < nst && t0 < n0 && t1 < n1;
-}
-
 // Accumulator element (mi, r) of a lane sits at row mi*32 + 8*(r/4) + 4*(lane/32) + r%4 of the
 // wave's 128-row sub-tile.  Inverse for one row offset `rel` (relative to the sub-tile, already
 // reduced by 4*(lane/32)): register index mi*16 + r, or -1 if this lane does not hold it.
@@ -588,7 +540,7 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward step 2: d_hidden[t][k] -= (g_t / (kQScale kWScale)) sum_{v in chunk} q[t][v] W16[v][k]
+// Backward step 2: d_hidden[t][k] -= (g_t / (kQScale s_w)) sum_{v in chunk} q[t][v] W16[v][k], W16 = s_w W
 // (the rows were initialised with the y-logit term)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict__ hdr,
@@ -617,6 +569,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     // k of one token, so updating from registers would touch 32-byte pieces of 32 different rows per
     // instruction; staged as [token][k] rows (pitch 1040 B: the 8 rows one LDS write cycle covers fall
     // into different banks), every global load and store covers one whole 1 KiB row segment.
+    const float wscale_inv = -1.0f / (kQScale * w_range_scale(hdr));
     for (int half = 0; half < 2; ++half) {
         __syncthreads();   // the ring (first pass) or the previous half has been consumed
         // wave w updates rows 32 w .. 32 w + 31 of this half in four batches of eight rows; a batch's
@@ -642,7 +595,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
             for (int ni = 0; ni < 4; ++ni) {
                 const int tloc = ni * 32 + (g.lane & 31);
                 const int64_t p = tt * kTile + half * 128 + tloc;
-                const float scale = (p < n_valid) ? gvec[p] * (-1.0f / (kQScale * kWScale)) : 0.0f;
+                const float scale = (p < n_valid) ? gvec[p] * wscale_inv : 0.0f;
                 unsigned char* row = lds + tloc * kHPitch + (g.wm * 128 + 4 * (g.lane >> 5)) * 4;
 #pragma unroll
                 for (int mi = 0; mi < 4; ++mi)
@@ -809,7 +762,7 @@ __global__ __launch_bounds__(256) void dw_onehot_kernel(const LossHeader* __rest
 // chip's power limit the bf16 matrix instruction sustains 9 % more than the fp16 one (measured on an
 // MFMA-only loop: 1.74 against 1.59 PFLOP/s).
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void transpose_kernel(const LossHeader* __restrict__ hdr,
+__global__ __launch_bounds__(256) void transpose_kernel(LossHeader* __restrict__ hdr,
                                                         const int32_t* __restrict__ gather,
                                                         const uint16_t* __restrict__ src, int64_t rows,
                                                         int d, int64_t rows_out, int token_rows,
@@ -824,6 +777,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const LossHeader* __rest
     const int k0 = blockIdx.y * 64;
     if (r0 >= fill_to) return;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    uint32_t amax = 0u;   // largest |x| seen, as bf16 bits (non-negative floats order as integers)
     for (int rr = ty; rr < 64; rr += 4) {
         const int64_t r = r0 + rr;
         uint16_t x = 0;
@@ -832,7 +786,11 @@ __global__ __launch_bounds__(256) void transpose_kernel(const LossHeader* __rest
             x = src[srow * d + k0 + tx];
         }
         tile[rr][tx] = x;
+        amax = max(amax, (uint32_t)(x & 0x7FFFu));
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, off, 64));
+    if (tx == 0 && amax != 0u) atomicMax(token_rows ? &hdr->hmax_bits : &hdr->wmax_bits, amax << 16);
     __syncthreads();
     for (int kk = ty; kk < 64; kk += 4) {
         const int64_t r = r0 + tx;
@@ -842,7 +800,8 @@ __global__ __launch_bounds__(256) void transpose_kernel(const LossHeader* __rest
 
 // ------------------------------------------------------------------------------------------
 // fp16 operand copies (once per call):
-//   W16[v][k] = kWScale W[v][k]           (zero rows for v >= V; exact: bf16 has fewer significand bits)
+//   W16[v][k] = s_w W[v][k]               (zero rows for v >= V; exact in fp16's normal range: bf16 has
+//                                          fewer significand bits; s_w = the range scale of W)
 //   H16[p][k] = s g_p H[row_map[p]][k]    (zero rows for p >= N up to the end of the last token tile;
 //                                          s = the global range scale of g)
 // One thread per 8 elements.
@@ -854,7 +813,7 @@ __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restri
                                                       int64_t rows_out, int d, int token_rows,
                                                       _Float16* __restrict__ dst) {
     int64_t nrows = rows, fill_to = rows_out;
-    float common = kWScale;
+    float common = w_range_scale(hdr);
     if (token_rows) {
         nrows = hdr->n_bwd;
         fill_to = (nrows + kTile - 1) / kTile * kTile;
@@ -891,7 +850,7 @@ pods_status reserve(const void* kernel, const char* what, int bytes = kLdsBytes)
 
 pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
     unsigned char* ws = a.workspace;
-    auto* hdr = reinterpret_cast<const LossHeader*>(ws + p.off_hdr);
+    auto* hdr = reinterpret_cast<LossHeader*>(ws + p.off_hdr);
     auto* row_map = reinterpret_cast<const int32_t*>(ws + p.off_rowmap);
     auto* wt = reinterpret_cast<uint16_t*>(ws + p.off_wtt);
     auto* ht = reinterpret_cast<uint16_t*>(ws + p.off_htt);

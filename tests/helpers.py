@@ -80,3 +80,36 @@ def check_loss(got, ref):
     assert_close_tensor("logp", got["logp"], ref["logp"])
     assert_close_tensor("d_hidden", got["d_hidden"], ref["d_hidden"])
     assert_close_tensor("d_w", got["d_w"], ref["d_w"])
+
+
+def softmax_term_magnitudes(case, grad_scale=1.0, gemm_dtype=np.float32, block=256):
+    """A[v, k] = sum over valid tokens t with y_t != v of |dz_tv| |h_tk|: the summed magnitudes of the terms
+    of d_w_lm[v, k] that come from the softmax part of the logit gradient (everything but the generated
+    token's own logit), from the oracle's per-token rows.  The matrix-core path rounds exactly these
+    terms' two factors to fp16 (unit roundoff 2^-11 each), so 2^-10 A bounds what that rounding can move
+    an element by, whatever cancellation its terms undergo."""
+    h, w, tok, lens = case["hidden"], case["w"], case["tokens"], case["lengths"].astype(np.int64)
+    R, T, d = h.shape
+    ii = np.concatenate([np.full(int(lens[i]), i, dtype=np.int64) for i in range(R)])
+    tt = np.concatenate([np.arange(int(lens[i]), dtype=np.int64) for i in range(R)])
+    A = np.zeros((w.shape[0], d))
+    for s in range(0, len(ii), block):
+        bi, bt = ii[s:s + block], tt[s:s + block]
+        hb = h[bi, bt]
+        cb = 1.0 / (R * lens[bi].astype(np.float64))
+        out = po.token_rows(hb, w, tok[bi, bt], case["old_logp"][bi, bt], case["adv"][bi], cb, case["clip_eps"],
+                            grad_scale, gemm_dtype)
+        mag = np.abs(out["dz"])
+        mag[np.arange(len(bi)), tok[bi, bt]] = 0.0
+        A += (mag.astype(gemm_dtype).T @ np.abs(hb).astype(gemm_dtype)).astype(np.float64)
+    return A
+
+
+def assert_close_dw_unit_scale(got, ref, A, rtol=RTOL, atol=ATOL):
+    """d_w_lm at a gradient scale where its terms are O(1): elementwise rtol / atol plus the worst-case fp16
+    rounding of the softmax terms (see softmax_term_magnitudes), and the norm-wise bars."""
+    diff = np.abs(got - ref)
+    bad = diff > rtol * np.abs(ref) + atol + 2.0 ** -10 * A
+    assert not bad.any(), f"d_w: {bad.sum()} elements outside the bound; max diff {diff.max():.3e}"
+    assert diff.max() <= rtol * np.abs(ref).max()
+    assert np.linalg.norm(got - ref) <= rtol * np.linalg.norm(ref)

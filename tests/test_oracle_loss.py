@@ -106,6 +106,9 @@ def test_clip_branches_and_zero_rows():
     assert np.all(out["d_hidden"][0] == 0) and np.all(out["d_hidden"][1] == 0)
     assert np.any(out["d_hidden"][2] != 0)
     assert np.all(out["d_hidden"][3] == 0)                           # zero advantage
+    # the mask of cut tokens: exactly the first two (a zero advantage is not "clipped")
+    assert out["clipped"][:, 0].tolist() == [True, True, False, False]
+    assert np.allclose(out["rho"][:, 0], [1.5, 0.5, 1.5, 1.0], rtol=1e-12)
     # loss value: clipped terms contribute (1+eps)*a, (1-eps)*a; third min(1.5*-1, 1.2*-1) = -1.5
     assert out["loss"] == pytest.approx(-(1.2 * 1.0 + 0.8 * -1.0 + 1.5 * -1.0 + 0.0) / 4, rel=1e-12)
 

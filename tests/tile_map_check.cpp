@@ -1,0 +1,55 @@
+// Host-side check of the workgroup-id -> tile mapping used by the token loss's matrix-core kernels
+// (paper_2504_13818_amd/csrc/tile_map.h, compiled here for the CPU): for an n0 x n1 tile grid, the ids
+// 0 .. super_grid_blocks(n0, n1) - 1 must name every tile exactly once and nothing outside the grid.
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "tile_map.h"
+
+extern "C" {
+
+// 0 if the mapping of an n0 x n1 grid is a bijection onto the tiles; otherwise a code:
+// 1 = an id accepted with coordinates outside the grid, 2 = a tile named twice, 3 = a tile never named,
+// 4 = the grid is not a whole number of rounds over the XCDs.
+// `grid` is the number of ids enumerated (the launch size); tile_map_check_one passes the mapping's own.
+int tile_map_check_ids(int64_t n0, int64_t n1, int64_t grid) {
+    if (grid % pods::kXcds != 0) return 4;
+    std::vector<unsigned char> seen((std::size_t)(n0 * n1), 0);
+    for (int64_t bid = 0; bid < grid; ++bid) {
+        int64_t t0 = -1, t1 = -1;
+        if (!pods::decode_tile(bid, n0, n1, t0, t1)) continue;
+        if (t0 < 0 || t0 >= n0 || t1 < 0 || t1 >= n1) return 1;
+        if (seen[(std::size_t)(t0 * n1 + t1)]++) return 2;
+    }
+    for (unsigned char s : seen)
+        if (s != 1) return 3;
+    return 0;
+}
+
+int tile_map_check_one(int64_t n0, int64_t n1) {
+    return tile_map_check_ids(n0, n1, pods::super_grid_blocks(n0, n1));
+}
+
+// Sweeps n0 in [n0_lo, n0_hi] (step n0_step) x n1 in [1, n1_hi]; returns the number of failing grids
+// and writes the first failing (n0, n1, code) to first[3].
+int64_t tile_map_check_range(int64_t n0_lo, int64_t n0_hi, int64_t n0_step, int64_t n1_hi, int64_t* first) {
+    int64_t bad = 0;
+#pragma omp parallel for schedule(dynamic) reduction(+ : bad)
+    for (int64_t n0 = n0_lo; n0 <= n0_hi; n0 += n0_step)
+        for (int64_t n1 = 1; n1 <= n1_hi; ++n1) {
+            const int code = tile_map_check_one(n0, n1);
+            if (code != 0) {
+#pragma omp critical
+                if (bad == 0 && first[2] == 0) { first[0] = n0; first[1] = n1; first[2] = code; }
+                ++bad;
+            }
+        }
+    return bad;
+}
+
+int64_t tile_map_blocks(int64_t n0, int64_t n1) { return pods::super_blocks(n0, n1); }
+int64_t tile_map_few_blocks(void) { return pods::kFewBlocks; }
+int64_t tile_map_grid(int64_t n0, int64_t n1) { return pods::super_grid_blocks(n0, n1); }
+
+}  // extern "C"
