@@ -22,9 +22,13 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 / fp16 MFMA peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
-KERNEL_SYMBOLS = {"token loss forward": "fwd_kernel", "token loss recompute": "recompute_kernel",
-                  "token loss d_hidden": "dh_kernel", "token loss d_w_lm": "dw_kernel",
-                  "pods_select": "select_kernel"}
+# Kernel names as rocprofv3 prints them, demangled or mangled, matched exactly (template arguments
+# included: the selector-stress launch is select_kernel<32, 8>, not the other group sizes' variants).
+KERNEL_SYMBOLS = {"token loss forward": (r"::fwd_kernel\(", r"\d+fwd_kernelE"),
+                  "token loss recompute": (r"::recompute_kernel\(", r"\d+recompute_kernelE"),
+                  "token loss d_hidden": (r"::dh_kernel\(", r"\d+dh_kernelE"),
+                  "token loss d_w_lm": (r"::dw_kernel\(", r"\d+dw_kernelE"),
+                  "pods_select": (r"::select_kernel<32, 8>\(", r"\d+select_kernelILi32ELi8EE")}
 PROBE_BYTES = 1 << 30         # the calibration copy reads and writes this many bytes
 
 
@@ -56,6 +60,7 @@ def summarize_traffic(fetch_csv, write_csv, out_path=TRAFFIC_FILE):
     copy kernel of known size."""
     import csv
     import collections
+    import re
 
     def load(path, counter):
         per = collections.defaultdict(list)
@@ -65,8 +70,8 @@ def summarize_traffic(fetch_csv, write_csv, out_path=TRAFFIC_FILE):
                 continue
             name, val = r["Kernel_Name"], float(r["Counter_Value"])
             dur = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
-            for label, sym in KERNEL_SYMBOLS.items():
-                if sym in name:
+            for label, patterns in KERNEL_SYMBOLS.items():
+                if any(re.search(pat, name) for pat in patterns):
                     per[label].append(val)
             if "MulFunctor" in name and "vectorized_elementwise_kernel" in name:
                 probe.append((dur, val))
@@ -206,6 +211,163 @@ def cpu_loss(inputs, cfg, tokens_sample=4096):
                        f"fp32 GEMM, fp64 reductions; forward + backward, {dt:.1f} s; cost is linear in tokens")
 
 
+def make_inputs(torch, inputs, cfg, dev):
+    """Synthetic inputs of one config, resident on the device."""
+    c = inputs.CONFIGS[cfg]
+    B, n, m, T, d, V = c["B"], c["n"], c["m"], c["T"], c["d"], c["V"]
+    R = B * m
+    rewards = torch.from_numpy(inputs.rewards(cfg)).to(dev)
+    lens_np = inputs.lengths(cfg)
+    lengths = torch.from_numpy(lens_np).to(dev)
+    tokens = torch.from_numpy(inputs.tokens(cfg, R, T, V)).to(dev)
+    hidden, w = inputs.dense_torch(cfg, dev)
+    cur = current_logp_torch(torch, hidden, w, tokens)
+    g = torch.Generator(device=dev)
+    g.manual_seed(inputs.seed_for(cfg, 5))
+    old_logp = (cur + 0.05 * torch.randn(cur.shape, generator=g, device=dev)).contiguous()
+    del cur
+    return dict(c=c, B=B, n=n, m=m, T=T, d=d, V=V, R=R, rewards=rewards, lens_np=lens_np, lengths=lengths,
+                tokens=tokens, hidden=hidden, w=w, old_logp=old_logp, n_valid=int(lens_np.sum()))
+
+
+GEMM_NAMES = ["token loss forward", "token loss recompute", "token loss d_hidden", "token loss d_w_lm"]
+
+
+def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False, with_skip=False):
+    """Times `steps` whole steps (pods_select + pods_advantage + grpo_token_loss_fwd_bwd) of one config, with
+    HIP events around every kernel launch."""
+    import numpy as np
+    x = make_inputs(torch, inputs, cfg, dev)
+    c, B, m, T, d, V, R, n_valid = x["c"], x["B"], x["m"], x["T"], x["d"], x["V"], x["R"], x["n_valid"]
+    dt = lib.PODS_BF16 if c["dtype"] == "bf16" else lib.PODS_F32
+    ws = torch.empty((lib.grpo_token_loss_workspace_bytes(R, T, d, V, dt),), dtype=torch.uint8, device=dev)
+    out = dict(loss=torch.empty(1, dtype=torch.float32, device=dev),
+               logp=torch.empty((R, T), dtype=torch.float32, device=dev),
+               d_hidden=torch.empty((R, T, d), dtype=torch.float32, device=dev),
+               d_w_lm=torch.empty((V, d), dtype=torch.float32, device=dev))
+    sel_idx = torch.empty((B, m), dtype=torch.int32, device=dev)
+    sel_k = torch.empty((B,), dtype=torch.int32, device=dev)
+    adv = torch.empty((B, m), dtype=torch.float32, device=dev)
+
+    def step(skip=False):
+        lib.pods_select(x["rewards"], m, sel_idx, sel_k)
+        lib.pods_advantage(x["rewards"], sel_idx, 0.0, adv)
+        lib.grpo_token_loss_fwd_bwd(x["hidden"], x["w"], x["tokens"], x["old_logp"], adv.view(-1), x["lengths"],
+                                    c["clip_eps"], 1.0, workspace=ws, out=out, skip_zero_advantage=skip)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    if traffic_probe:
+        px = torch.ones(PROBE_BYTES // 4, dtype=torch.float32, device=dev)
+        py = torch.empty_like(px)
+        torch.mul(px, 1.0, out=py)
+        torch.cuda.synchronize()
+        del px, py
+    lib.pods_profile_enable(True)               # HIP events around every launch, on the launch stream
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # same stream as the launches
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(steps):
+        step()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = lib.pods_profile_read()
+    lib.pods_profile_enable(False)
+    ms_per_step = wall * 1e3 / steps
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    loss_val = float(out["loss"].cpu()[0])
+    assert np.isfinite(loss_val)
+    report = lib.grpo_token_loss_report(ws)
+    assert report["valid_tokens"] == n_valid and report["bad_tokens"] == 0 and report["bad_lengths"] == 0
+
+    per = {}
+    for name, ms in prof:
+        e = per.setdefault(name, [0, 0.0])
+        e[0] += 1
+        e[1] += ms
+    kernels = {k: dict(launches_per_step=v[0] / steps, ms_per_step=v[1] / steps, avg_ms=v[1] / v[0])
+               for k, v in per.items()}
+    flops_family = 2.0 * n_valid * d * V        # each of the four contractions, per step
+    for k in GEMM_NAMES:
+        if k in kernels:
+            kernels[k]["tflops"] = flops_family / (kernels[k]["ms_per_step"] * 1e-3) / 1e12
+    dominant = max((k for k in GEMM_NAMES if k in kernels), key=lambda k: kernels[k]["ms_per_step"])
+    dk = kernels[dominant]
+    flops_per_launch = flops_family / dk["launches_per_step"]
+    achieved = flops_per_launch / (dk["avg_ms"] * 1e-3) / 1e12
+    gpu_ms = sum(v["ms_per_step"] for v in kernels.values())
+    roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_BF16_TFLOPS, traffic=recorded_traffic(dominant) if cfg == 1 else None,
+                    flops_per_launch=flops_per_launch, avg_launch_ms=dk["avg_ms"],
+                    path_executed_tflops=4 * flops_family / (gpu_ms * 1e-3) / 1e12,
+                    path_executed_frac=4 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                    path_model_frac=3 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
+    res = dict(workload=f"configs[{cfg}] {c['name']}: B={B} n={x['n']} m={m} R={R} T={T} "
+                        f"valid_tokens={n_valid} d={d} V={V} {c['dtype']} eps={c['clip_eps']}",
+               value=n_valid / (ms_per_step * 1e-3), unit="tokens/s", steps=steps, warmup=warmup,
+               ms_per_step=ms_per_step, ms_per_step_median=step_ms[len(step_ms) // 2], ms_per_step_min=step_ms[0],
+               roofline=roofline, kernels=kernels, loss=loss_val,
+               clip_fraction=report["clipped_tokens"] / max(n_valid, 1), n_valid=n_valid)
+
+    if with_skip:
+        # Beside the headline (which back-propagates every valid token): the same step with the rollouts
+        # of prompts without reward variance (advantage exactly 0) left out of the backward pass.
+        skip_steps = max(3, steps // 4)
+        step(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(skip_steps):
+            step(True)
+        torch.cuda.synchronize()
+        skip_ms = (time.perf_counter() - t0) * 1e3 / skip_steps
+        live = int(x["lens_np"][(adv.view(-1) != 0).cpu().numpy()].sum())
+        res["skip_zero_advantage"] = dict(
+            ms_per_step=skip_ms, steps=skip_steps, valid_tokens=n_valid, tokens_back_propagated=live,
+            note="not the headline: value counts every valid token and is measured without skipping")
+    return res
+
+
+def context_numbers(lib, torch, dev, n_tokens, d, vc=8192):
+    """Numbers measured in this process beside the token loss's own, as context for its fraction of the
+    published matrix-core peak (never the target): the vendor GEMM (torch.matmul, bf16) on the shape of one
+    d_w_lm launch, and a loop of matrix instructions with no memory traffic at all."""
+    import numpy as np
+    ctx = {}
+    n_tok = (n_tokens // 256) * 256
+    a = torch.randn((n_tok, vc), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    b = torch.randn((n_tok, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    c = torch.empty((vc, d), device=dev, dtype=torch.bfloat16)
+    at = a.t()
+    for _ in range(2):
+        torch.matmul(at, b, out=c)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+    ev[0].record()
+    for i in range(5):
+        torch.matmul(at, b, out=c)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(5)]))
+    tf = 2.0 * n_tok * vc * d / (ms * 1e-3) / 1e12
+    ctx["vendor_gemm"] = dict(what=f"torch.matmul bf16, [{vc} x {n_tok}] . [{n_tok} x {d}] (one d_w_lm launch's shape), "
+                                   "random normal operands, median of 5", ms=ms, tflops=tf, frac_of_peak=tf / PEAK_BF16_TFLOPS)
+    del a, b, c, at
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    lib.pods_profile_mfma_only(256, 2000, sink)
+    torch.cuda.synchronize()
+    lib.pods_profile_enable(True)
+    flops = [lib.pods_profile_mfma_only(2048, 20000, sink) for _ in range(3)]
+    prof = lib.pods_profile_read()
+    lib.pods_profile_enable(False)
+    ms = float(np.median([t for _, t in prof]))
+    tf = flops[0] / (ms * 1e-3) / 1e12
+    ctx["mfma_only"] = dict(what="v_mfma_f32_32x32x16_bf16 on register operands, 2048 workgroups x 4 wavefronts x 640000 "
+                                 "instructions, no loads; median of 3 launches", ms=ms, tflops=tf,
+                            frac_of_peak=tf / PEAK_BF16_TFLOPS)
+    return ctx
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -213,6 +375,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, choices=[1, 2, 4])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="skip the other loss configs, the context numbers and the gather figure")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run a 1 GiB copy kernel, the calibration for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--summarize-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
@@ -226,7 +390,6 @@ def main():
               "(prompt groups and kept rollouts shard across GPUs without exchange; only d_w_lm is reduced).", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     import paper_2504_13818_amd as lib
@@ -236,128 +399,53 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = args.config
+    head = run_config(lib, torch, inputs, cfg, args.steps, args.warmup, dev, traffic_probe=args.traffic_probe,
+                      with_skip=True)
+    torch.cuda.empty_cache()
     c = inputs.CONFIGS[cfg]
-    B, n, m, T, d, V = c["B"], c["n"], c["m"], c["T"], c["d"], c["V"]
-    R = B * m
-
-    rewards = torch.from_numpy(inputs.rewards(cfg)).to(dev)
-    lens_np = inputs.lengths(cfg)
-    n_valid = int(lens_np.sum())
-    lengths = torch.from_numpy(lens_np).to(dev)
-    tokens = torch.from_numpy(inputs.tokens(cfg, R, T, V)).to(dev)
-    hidden, w = inputs.dense_torch(cfg, dev)
-    cur = current_logp_torch(torch, hidden, w, tokens)
-    g = torch.Generator(device=dev)
-    g.manual_seed(inputs.seed_for(cfg, 5))
-    old_logp = (cur + 0.05 * torch.randn(cur.shape, generator=g, device=dev)).contiguous()
-    del cur
-
-    dt = lib.PODS_BF16 if c["dtype"] == "bf16" else lib.PODS_F32
-    ws = torch.empty((lib.grpo_token_loss_workspace_bytes(R, T, d, V, dt),), dtype=torch.uint8, device=dev)
-    out = dict(loss=torch.empty(1, dtype=torch.float32, device=dev),
-               logp=torch.empty((R, T), dtype=torch.float32, device=dev),
-               d_hidden=torch.empty((R, T, d), dtype=torch.float32, device=dev),
-               d_w_lm=torch.empty((V, d), dtype=torch.float32, device=dev))
-    sel_idx = torch.empty((B, m), dtype=torch.int32, device=dev)
-    sel_k = torch.empty((B,), dtype=torch.int32, device=dev)
-    adv = torch.empty((B, m), dtype=torch.float32, device=dev)
-
-    def step():
-        lib.pods_select(rewards, m, sel_idx, sel_k)
-        lib.pods_advantage(rewards, sel_idx, 0.0, adv)
-        lib.grpo_token_loss_fwd_bwd(hidden, w, tokens, old_logp, adv.view(-1), lengths, c["clip_eps"],
-                                    1.0, workspace=ws, out=out)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if args.traffic_probe:
-        px = torch.ones(PROBE_BYTES // 4, dtype=torch.float32, device=dev)
-        py = torch.empty_like(px)
-        torch.mul(px, 1.0, out=py)
-        torch.cuda.synchronize()
-        del px, py
-    lib.pods_profile_enable(True)               # HIP events around every launch, on the launch stream
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # same stream as the launches
-    t0 = time.perf_counter()
-    marks[0].record()
-    for i in range(args.steps):
-        step()
-        marks[i + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    prof = lib.pods_profile_read()
-    lib.pods_profile_enable(False)
-    ms_per_step = wall * 1e3 / args.steps
-    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    loss_val = float(out["loss"].cpu()[0])
-    assert np.isfinite(loss_val)
-
-    per = {}
-    for name, ms in prof:
-        e = per.setdefault(name, [0, 0.0])
-        e[0] += 1
-        e[1] += ms
-    kernels = {k: dict(launches_per_step=v[0] / args.steps, ms_per_step=v[1] / args.steps,
-                       avg_ms=v[1] / v[0]) for k, v in per.items()}
-    gemm_names = ["token loss forward", "token loss recompute", "token loss d_hidden", "token loss d_w_lm"]
-    flops_family = 2.0 * n_valid * d * V        # each of the four contractions, per step
-    for k in gemm_names:
-        if k in kernels:
-            kernels[k]["tflops"] = flops_family / (kernels[k]["ms_per_step"] * 1e-3) / 1e12
-    dominant = max((k for k in gemm_names if k in kernels), key=lambda k: kernels[k]["ms_per_step"])
-    dk = kernels[dominant]
-    flops_per_launch = flops_family / dk["launches_per_step"]
-    achieved = flops_per_launch / (dk["avg_ms"] * 1e-3) / 1e12
-    gpu_ms = sum(v["ms_per_step"] for v in kernels.values())
-    roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_BF16_TFLOPS, traffic=recorded_traffic(dominant),
-                    flops_per_launch=flops_per_launch, avg_launch_ms=dk["avg_ms"],
-                    path_executed_tflops=4 * flops_family / (gpu_ms * 1e-3) / 1e12,
-                    path_executed_frac=4 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                    path_model_frac=3 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
-
-    # Beside the headline (which back-propagates every valid token): the same step with the rollouts
-    # of prompts without reward variance (advantage exactly 0) left out of the backward pass.
-    def step_skip():
-        lib.pods_select(rewards, m, sel_idx, sel_k)
-        lib.pods_advantage(rewards, sel_idx, 0.0, adv)
-        lib.grpo_token_loss_fwd_bwd(hidden, w, tokens, old_logp, adv.view(-1), lengths, c["clip_eps"],
-                                    1.0, workspace=ws, out=out, skip_zero_advantage=True)
-    skip_steps = max(3, args.steps // 4)
-    step_skip()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(skip_steps):
-        step_skip()
-    torch.cuda.synchronize()
-    skip_ms = (time.perf_counter() - t0) * 1e3 / skip_steps
-    live = int(lens_np[(adv.view(-1) != 0).cpu().numpy()].sum())
-    skip = dict(ms_per_step=skip_ms, steps=skip_steps, valid_tokens=n_valid, tokens_back_propagated=live,
-                note="not the headline: value counts every valid token and is measured without skipping")
 
     selector = time_selector(lib, torch, inputs, args.steps)
     result = {
         "metric": "GRPO token-loss fwd+bwd tokens/s (% MFMA peak); pods_select groups/s (% HBM)",
-        "value": n_valid / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_median": step_ms[len(step_ms) // 2],
-        "ms_per_step_min": step_ms[0], "higher_is_better": True, "scaling": "weak",
+        "value": head["value"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "ms_per_step_median": head["ms_per_step_median"],
+        "ms_per_step_min": head["ms_per_step_min"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": c["dtype"], "data": "synthetic",
-        "config": {"workload": f"configs[{cfg}] {c['name']}: B={B} n={n} m={m} R={R} T={T} "
-                               f"valid_tokens={n_valid} d={d} V={V} {c['dtype']} eps={c['clip_eps']}",
+        "config": {"workload": head["workload"],
                    "step": "pods_select + pods_advantage + grpo_token_loss_fwd_bwd",
                    "arithmetic": "logits: bf16 MFMA (v_mfma_f32_32x32x16_bf16); gradients: fp16 MFMA on exact fp16 copies of "
                                  "the bf16 inputs and an fp16 softmax operand; fp32 accumulation; fp64 selector scores"},
-        "roofline": roofline,
-        "kernels": kernels,
+        "roofline": head["roofline"],
+        "kernels": head["kernels"],
         "selector": selector,
-        "gather": time_gather(lib, torch, args.steps),
-        "skip_zero_advantage": skip,
-        "loss": loss_val,
+        "skip_zero_advantage": head["skip_zero_advantage"],
+        "loss": head["loss"],
+        "clip_fraction": head["clip_fraction"],
     }
+    if not args.only_headline:
+        # the other two loss workloads of the metric, a few steps each (not the headline value)
+        others = {}
+        for other in (1, 2, 4):
+            if other == cfg:
+                continue
+            r = run_config(lib, torch, inputs, other, max(3, args.steps // 4), 1, dev)
+            torch.cuda.empty_cache()
+            rf = r["roofline"]
+            others[str(other)] = dict(
+                workload=r["workload"], tokens_per_s=r["value"], ms_per_step=r["ms_per_step"], steps=r["steps"],
+                warmup=r["warmup"], dominant_kernel=rf["kernel"], dominant_kernel_frac=rf["frac"],
+                path_executed_frac=rf["path_executed_frac"], path_model_frac=rf["path_model_frac"],
+                gemm_tflops={k: r["kernels"][k]["tflops"] for k in GEMM_NAMES if k in r["kernels"]},
+                loss=r["loss"], clip_fraction=r["clip_fraction"])
+        result["configs"] = others
+        result["gather"] = time_gather(lib, torch, args.steps)
+        result["context"] = context_numbers(lib, torch, dev, head["n_valid"], c["d"])
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_loss(inputs, cfg)
         result["selector"]["cpu_baseline"] = cpu_selector(inputs)
+        if not args.only_headline:
+            for other in result["configs"]:
+                result["configs"][other]["cpu_baseline"] = cpu_loss(inputs, int(other), tokens_sample=2048)
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result))

@@ -24,6 +24,15 @@ pods_status pods_profile_enable(int32_t enable);
 int32_t pods_profile_count(void);
 pods_status pods_profile_get(int32_t i, const char** name, float* ms);
 
+/* Context for the token loss's matrix-core roofline: one launch of `workgroups` workgroups (4 wavefronts
+ * each, one workgroup per compute unit at a time) that issue nothing but v_mfma_f32_32x32x16_bf16 on
+ * register operands, `iters` x 32 per wavefront.  What this sustains is the ceiling the chip's clock and
+ * power management leave to ANY kernel, beside the published peak.  Timed like every other launch (enable
+ * the hooks, then read the record named "mfma only").
+ *   sink   [1] float32 device, practically never written;  flops: HOST, out, floating-point operations of the launch */
+pods_status pods_profile_mfma_only(int32_t workgroups, int32_t iters, float* sink, double* flops /* host */,
+                                   void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = ("pods_select", "pods_downsample", "pods_advantage", "pods_ad
                     "grpo_token_loss_workspace_min_bytes", "grpo_token_loss_workspace_used_bytes",
                     "grpo_token_loss_fwd_bwd", "grpo_token_loss_fwd_bwd_static",
                     "grpo_token_loss_static_workspace_bytes", "grpo_token_loss_report", "pods_check_rewards",
-                    "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get")
+                    "pods_last_error", "pods_profile_enable", "pods_profile_count", "pods_profile_get", "pods_profile_mfma_only")
 
 _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
 
@@ -102,6 +102,8 @@ def load():
     lib.pods_profile_count.argtypes = []
     lib.pods_profile_get.restype = ctypes.c_int
     lib.pods_profile_get.argtypes = [_i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_f32)]
+    lib.pods_profile_mfma_only.restype = ctypes.c_int
+    lib.pods_profile_mfma_only.argtypes = [_i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
     _lib = lib
     return lib
 
@@ -396,3 +398,10 @@ def pods_check_rewards(rewards, report=None, stream=None):
         report = torch.empty((2,), dtype=torch.int32, device=rewards.device)
     _check(load().pods_check_rewards(_ptr(rewards), B, n, _ptr(report), _stream(stream)))
     return report
+
+
+def pods_profile_mfma_only(workgroups: int, iters: int, sink, stream=None) -> float:
+    """Launch the matrix-core-only loop of include/pods_profile.h; returns its floating-point operations."""
+    flops = ctypes.c_double()
+    _check(load().pods_profile_mfma_only(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream(stream)))
+    return float(flops.value)

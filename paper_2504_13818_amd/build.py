@@ -19,7 +19,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.j
 # saying so spares a canonicalising v_max_f64 in front of every v_min_f64 of the network.
 PER_FILE = {"select.hip": ["-ffp-contract=off", "-fno-honor-nans"], "advantage.hip": ["-ffp-contract=off"],
             "downsample_gather.hip": ["-ffp-contract=off"]}
-SOURCES = ["api.hip", "select.hip", "advantage.hip", "downsample_gather.hip", "loss.hip", "loss_simple.hip", "loss_mfma.hip"]
+SOURCES = ["api.hip", "profile.hip", "select.hip", "advantage.hip", "downsample_gather.hip", "loss.hip", "loss_simple.hip", "loss_mfma.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -1,10 +1,8 @@
 // C ABI of the PODS HIP library: argument checks, then dispatch to the kernel families.
 #include "common.h"
 #include "loss.h"
-#include "pods_profile.h"
 
 #include <mutex>
-#include <vector>
 
 namespace pods {
 char* error_buffer() {
@@ -12,40 +10,6 @@ char* error_buffer() {
     return buf;
 }
 
-namespace {
-struct Stage { const char* name; hipEvent_t start, stop; };
-struct Profile {
-    bool enabled = false;
-    size_t used = 0;             // stages recorded since the last enable / reset
-    std::vector<Stage> stages;   // event pairs are created once and reused
-};
-Profile& profile() {
-    static thread_local Profile p;
-    return p;
-}
-}  // namespace
-
-void profile_stage_begin(const char* name, hipStream_t stream) {
-    Profile& p = profile();
-    if (!p.enabled) return;
-    if (p.used == p.stages.size()) {
-        Stage s{name, nullptr, nullptr};
-        if (hipEventCreate(&s.start) != hipSuccess || hipEventCreate(&s.stop) != hipSuccess) {
-            p.enabled = false;
-            return;
-        }
-        p.stages.push_back(s);
-    }
-    p.stages[p.used].name = name;
-    (void)hipEventRecord(p.stages[p.used].start, stream);
-}
-
-void profile_stage_end(hipStream_t stream) {
-    Profile& p = profile();
-    if (!p.enabled || p.used >= p.stages.size()) return;
-    (void)hipEventRecord(p.stages[p.used].stop, stream);
-    ++p.used;
-}
 }  // namespace pods
 
 using namespace pods;
@@ -53,33 +17,6 @@ using namespace pods;
 extern "C" {
 
 const char* pods_last_error(void) { return error_buffer(); }
-
-pods_status pods_profile_enable(int32_t enable) {
-    auto& p = profile();
-    p.enabled = enable != 0;
-    p.used = 0;
-    if (!p.enabled) {   // switched off: the events go too
-        for (Stage& s : p.stages) {
-            (void)hipEventDestroy(s.start);
-            (void)hipEventDestroy(s.stop);
-        }
-        p.stages.clear();
-    }
-    return PODS_OK;
-}
-
-int32_t pods_profile_count(void) { return (int32_t)profile().used; }
-
-pods_status pods_profile_get(int32_t i, const char** name, float* ms) {
-    auto& p = profile();
-    if (i < 0 || (size_t)i >= p.used || name == nullptr || ms == nullptr)
-        return fail(PODS_ERR_INVALID_ARG, "pods_profile_get: index %d outside [0, %zu)", i, p.used);
-    hipError_t e = hipEventSynchronize(p.stages[i].stop);
-    if (e == hipSuccess) e = hipEventElapsedTime(ms, p.stages[i].start, p.stages[i].stop);
-    if (e != hipSuccess) return fail(PODS_ERR_RUNTIME, "pods_profile_get: %s", hipGetErrorString(e));
-    *name = p.stages[i].name;
-    return PODS_OK;
-}
 
 pods_status pods_select(const float* rewards, int32_t B, int32_t n, int32_t m, int32_t* sel_idx,
                         int32_t* sel_k, void* stream) {
