@@ -25,7 +25,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
 # Kernel names as rocprofv3 prints them, demangled or mangled, matched exactly (template arguments
 # included: the selector-stress launch is select_kernel<32, 8>, not the other group sizes' variants).
 KERNEL_SYMBOLS = {"token loss forward": (r"::fwd_kernel\(", r"\d+fwd_kernelE"),
-                  "token loss recompute": (r"::recompute_kernel\(", r"\d+recompute_kernelE"),
+                  "token loss rescale": (r"::rescale_kernel\(", r"\d+rescale_kernelE"),
                   "token loss d_hidden": (r"::dh_kernel\(", r"\d+dh_kernelE"),
                   "token loss d_w_lm": (r"::dw_kernel\(", r"\d+dw_kernelE"),
                   "pods_select": (r"::select_kernel<32, 8>\(", r"\d+select_kernelILi32ELi8EE")}
@@ -230,7 +230,7 @@ def make_inputs(torch, inputs, cfg, dev):
                 tokens=tokens, hidden=hidden, w=w, old_logp=old_logp, n_valid=int(lens_np.sum()))
 
 
-GEMM_NAMES = ["token loss forward", "token loss recompute", "token loss d_hidden", "token loss d_w_lm"]
+GEMM_NAMES = ["token loss forward", "token loss d_hidden", "token loss d_w_lm"]
 
 
 def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False, with_skip=False):
@@ -289,7 +289,7 @@ def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False,
         e[1] += ms
     kernels = {k: dict(launches_per_step=v[0] / steps, ms_per_step=v[1] / steps, avg_ms=v[1] / v[0])
                for k, v in per.items()}
-    flops_family = 2.0 * n_valid * d * V        # each of the four contractions, per step
+    flops_family = 2.0 * n_valid * d * V        # each of the three contractions, per step
     for k in GEMM_NAMES:
         if k in kernels:
             kernels[k]["tflops"] = flops_family / (kernels[k]["ms_per_step"] * 1e-3) / 1e12
@@ -301,8 +301,10 @@ def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False,
     roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=achieved / PEAK_BF16_TFLOPS, traffic=recorded_traffic(dominant) if cfg == 1 else None,
                     flops_per_launch=flops_per_launch, avg_launch_ms=dk["avg_ms"],
-                    path_executed_tflops=4 * flops_family / (gpu_ms * 1e-3) / 1e12,
-                    path_executed_frac=4 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                    # the path executes the method's three contractions (logits, d_hidden, d_w_lm: 6 N d V) and no
+                    # recomputation, so executed and algorithmic floating-point operations coincide
+                    path_executed_tflops=3 * flops_family / (gpu_ms * 1e-3) / 1e12,
+                    path_executed_frac=3 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                     path_model_frac=3 * flops_family / (gpu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
     res = dict(workload=f"configs[{cfg}] {c['name']}: B={B} n={x['n']} m={m} R={R} T={T} "
                         f"valid_tokens={n_valid} d={d} V={V} {c['dtype']} eps={c['clip_eps']}",

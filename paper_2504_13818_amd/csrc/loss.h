@@ -72,49 +72,57 @@ __device__ __forceinline__ float pow2(int e) {
 // Power-of-two range scales of the two fp16 gradient operands (exact for bf16 data that stays in fp16's
 // normal range, i.e. within 2^-22 of the largest element):
 //   W16 = fp16(s_w W),  s_w brings max |W| into [2^8, 2^9)
-//   H16 = fp16(s_h g_t h_t),  s_h brings (max |g|) (max |h|) below 2^14 (and at least to 2^12)
+//   H16 = fp16(s_h g_t h_t),  s_h brings (max |g|) (max |h|) below 2^14 (and at least to 2^12); the
+//         maximum of |g| is taken per token block, whose d_w_lm contribution is scaled back by 1 / s_h
 __device__ __forceinline__ float w_range_scale(const LossHeader* hdr) {
     if (hdr->wmax_bits == 0u) return 1.0f;
     return pow2(8 - float_exponent(hdr->wmax_bits));
 }
-__device__ __forceinline__ float g_range_scale(const LossHeader* hdr) {
-    if (hdr->gmax_bits == 0u || hdr->hmax_bits == 0u) return 1.0f;
-    return pow2(12 - float_exponent(hdr->gmax_bits) - float_exponent(hdr->hmax_bits));
+__device__ __forceinline__ float g_range_scale(uint32_t gmax_bits, const LossHeader* hdr) {
+    if (gmax_bits == 0u || hdr->hmax_bits == 0u) return 1.0f;
+    return pow2(12 - float_exponent(gmax_bits) - float_exponent(hdr->hmax_bits));
 }
 
 // Fixed power-of-two scale of the fp16 softmax operand of the two gradient contractions.
 constexpr float kQScale = 16384.0f;  // q = kQScale softmax (0 at v = y): 0 <= q <= 2^14
 
 constexpr int kTile = 256;          // token / vocab / hidden tile edge of the matrix-core kernels
-constexpr int kDefaultVocabChunk = 8192;
+constexpr int kDefaultVocabChunk = 8192;    // vocabulary columns per forward launch of the matrix-core path
+constexpr int kDefaultTokenBlock = 32768;   // packed token rows whose softmax numerators are held at a time
 
 struct LossPlan {
     int64_t ncap;     // R*T
     int64_t ncap_ld;  // ncap rounded up to kTile: rows of the per-token arrays
     bool mfma;        // bf16 inputs with d % 64 == 0 take the matrix-core path
-    int slots;        // forward partial slots per token
-    int vc;           // vocabulary chunk of the backward pass (multiple of kTile); 0 on the plain path
-    int nchunks;
-    int64_t ldq;      // row pitch of q in elements: vc plus one tile, so rows do not sit a power of two apart
-    int64_t vld;      // rows of the fp16 weight copy = nchunks * vc (zero past V)
-    int64_t vld_t;    // columns of the transposed fp16 weight copy = V rounded up to kTile
+    int slots;        // forward partial slots per token (one per vocabulary tile on the matrix-core path)
+    int64_t nb;       // matrix-core path: packed token rows per block (multiple of kTile); the block's softmax
+                      // numerators q[nb][ldq] are the only [tokens, vocabulary]-shaped array that ever exists
+    int nblocks;      // token blocks = ceil(ncap_ld / nb); 1 on the plain path
+    int64_t ldq;      // row pitch of q in elements: the padded vocabulary plus one tile, so rows do not sit a
+                      // power of two apart
+    int64_t vld;      // V rounded up to kTile: rows of the fp16 weight copy, columns of the transposed one
     int loss_blocks;
-    size_t off_hdr, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_pmax, off_psum,
+    size_t off_hdr, off_gmax, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_pmax, off_psum,
         off_losspart, off_wtt, off_htt, off_wt, off_ht, off_dz, total;
 };
 
 // mode 0: recommended size; mode 1: minimum size; otherwise `mode` is the number of bytes
-// available and the largest vocabulary chunk that fits is chosen.
+// available and the largest token block (up to the recommended one) that fits is chosen.
 LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, size_t mode);
 
 pods_status run_loss(const LossArgs& a);
+
+// Surrogate step (loss.hip) for the packed rows [row0, row0 + nrows): log-sum-exp from the forward partials,
+// the clipped objective, g, the y-logit coefficient, log-probs, loss partial sums; max |g| of the rows goes to
+// entry `block` of the per-block maxima.
+pods_status launch_surrogate(const LossArgs& a, const LossPlan& p, int64_t row0, int64_t nrows, int block);
 
 // Plain kernels (fp32 arithmetic, any shape): loss_simple.hip
 pods_status simple_forward(const LossArgs& a, const LossPlan& p);
 pods_status simple_backward(const LossArgs& a, const LossPlan& p);
 
-// Matrix-core kernels (bf16 inputs): loss_mfma.hip
-pods_status mfma_forward(const LossArgs& a, const LossPlan& p);
-pods_status mfma_backward(const LossArgs& a, const LossPlan& p);
+// Matrix-core kernels (bf16 inputs): loss_mfma.hip.  Forward, surrogate and backward, token block by
+// token block.
+pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p);
 
 }  // namespace pods

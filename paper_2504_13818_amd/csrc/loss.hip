@@ -29,65 +29,40 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     p.off_pmax = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
     p.off_psum = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
     p.off_losspart = take(sizeof(double) * (size_t)p.loss_blocks);
+    // per-block maxima of |g|: one entry per kTile rows covers every possible block size
+    p.off_gmax = take(sizeof(uint32_t) * (size_t)(p.ncap_ld / kTile));
     if (!p.mfma) {
-        p.vc = 0; p.nchunks = 0; p.ldq = 0; p.vld = 0; p.vld_t = 0;
+        p.nb = p.ncap_ld; p.nblocks = 1; p.ldq = 0; p.vld = 0;
         p.off_wtt = p.off_htt = p.off_wt = p.off_ht = p.off_dz = off;
         p.total = off;
         return p;
     }
     const int64_t vround = ((int64_t)V + kTile - 1) / kTile * kTile;
-    p.vld_t = vround;
-    p.off_wtt = take(2 * (size_t)d * (size_t)vround);        // transposed fp16 weight, [vround/256][d][256]
-    p.off_htt = take(2 * (size_t)d * (size_t)p.ncap_ld);     // transposed fp16 hidden, [ncap_ld/256][d][256]
-    // Fixed part: fp16 weight copy (vld rows, at most vround + vc) and fp16 packed, g-scaled hidden.
-    auto total_for = [&](int vc, LossPlan& q) {
-        size_t o = off;
-        auto tk = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
-        q.vc = vc;
-        q.nchunks = (int)ceil_div(vround, vc);
-        q.vld = (int64_t)q.nchunks * vc;
-        q.off_wt = tk(2 * (size_t)d * (size_t)q.vld);
-        q.off_ht = tk(2 * (size_t)d * (size_t)p.ncap_ld);
-        q.ldq = vc + kTile;
-        q.off_dz = tk(2 * (size_t)p.ncap_ld * (size_t)q.ldq);
-        q.total = o;
-    };
-    int vc;
+    p.vld = vround;
+    p.ldq = vround + kTile;
+    p.off_wtt = take(2 * (size_t)d * (size_t)vround);        // transposed bf16 weight, [vround/256][d][256]
+    p.off_htt = take(2 * (size_t)d * (size_t)p.ncap_ld);     // transposed bf16 hidden, [ncap_ld/256][d][256]
+    p.off_wt = take(2 * (size_t)d * (size_t)vround);         // fp16 weight copy (zero rows past V)
+    p.off_ht = take(2 * (size_t)d * (size_t)p.ncap_ld);      // fp16 packed, g-scaled hidden
+    p.off_dz = off;                                          // q[nb][ldq] fp16, the last array
+    const size_t row_bytes = 2 * (size_t)p.ldq;
+    const int64_t rec_nb = p.ncap_ld < kDefaultTokenBlock ? p.ncap_ld : kDefaultTokenBlock;
+    int64_t nb;
     if (mode == 0) {
-        // The d_w_lm launch of a chunk has (vc / 256) x ceil(d / 256) tiles of equal, long duration: pick
-        // the chunk, near the default, whose tile count fills whole rounds of the 256 CUs best
-        // (d = 3584: 36 x 14 = 504 tiles, not 32 x 14 = 448).
-        const int64_t nd = ((int64_t)d + kTile - 1) / kTile;
-        const int64_t nv0 = kDefaultVocabChunk / kTile;
-        int64_t best_nv = nv0;
-        double best_eff = -1.0;
-        for (int64_t nv = nv0 - nv0 / 4; nv <= nv0 + nv0 / 4; ++nv) {
-            const int64_t tiles = nv * nd;
-            const double eff = (double)tiles / (double)((tiles + 255) / 256 * 256);
-            const bool closer = llabs(nv - nv0) < llabs(best_nv - nv0);
-            if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && closer)) { best_eff = eff; best_nv = nv; }
-        }
-        const int64_t want = best_nv * kTile;
-        vc = (int)(vround < want ? vround : want);
+        nb = rec_nb;
     } else if (mode == 1) {
-        vc = kTile;
+        nb = kTile;
     } else {
-        // A caller-given workspace at least as large as the recommendation gets the recommended chunk.
-        // Below it: the largest chunk (at most four default chunks) whose layout fits.  The layout is not
-        // monotone in the chunk (the fp16 weight copy has nchunks * vc rows, which can grow when vc
-        // shrinks), so every candidate is laid out and checked; vc = kTile is the minimum the entry point
-        // has already checked against.
-        const LossPlan rec = plan_loss(R, T, d, V, dt, 0);
-        if (rec.total <= mode) return rec;
-        const int64_t cap = vround < 4 * kDefaultVocabChunk ? vround : 4 * kDefaultVocabChunk;
-        vc = kTile;
-        LossPlan q = p;
-        for (int64_t c = cap; c > kTile; c -= kTile) {
-            total_for((int)c, q);
-            if (q.total <= mode) { vc = (int)c; break; }
-        }
+        // the largest block (whole tiles, at most the recommended one) whose q fits in what is left;
+        // one tile of rows is the minimum the entry point has already checked against
+        const size_t left = mode > off ? mode - off : 0;
+        nb = (int64_t)(left / row_bytes) / kTile * kTile;
+        if (nb > rec_nb) nb = rec_nb;
+        if (nb < kTile) nb = kTile;
     }
-    total_for(vc, p);
+    p.nb = nb;
+    p.nblocks = (int)ceil_div(p.ncap_ld, nb);
+    p.total = align_up(off + (size_t)nb * row_bytes, 256);
     return p;
 }
 
@@ -101,11 +76,13 @@ __global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t* __res
                                                             const float* __restrict__ adv, int skip,
                                                             int R, int T,
                                                             int32_t* __restrict__ offsets,
+                                                            uint32_t* __restrict__ gmax_block, int ngmax,
                                                             LossHeader* __restrict__ hdr) {
     __shared__ int32_t wave_tot[16];
     __shared__ int32_t carry;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) carry = 0;
+    for (int b = tid; b < ngmax; b += 1024) gmax_block[b] = 0u;
     __syncthreads();
     int32_t n_live = 0;
     for (int pass = 0; pass < (skip ? 2 : 1); ++pass) {
@@ -192,35 +169,66 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
     }
 }
 
-// Per valid token: combine the forward partials into log-sum-exp, then the surrogate of
+// Per valid token of the rows [row0, row_end): the forward pass's partial (max, sum exp) pairs, one per
+// vocabulary tile, merged into log-sum-exp.  64 tokens per workgroup; the four waves take every fourth
+// partial each (coalesced across tokens, many loads in flight) and are merged through LDS.
+__global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__ hdr,
+                                                  const float* __restrict__ pmax,
+                                                  const float* __restrict__ psum, int slots,
+                                                  int64_t slot_stride, int64_t row0, int64_t row_end,
+                                                  float* __restrict__ lse_out) {
+    __shared__ float sm[4][64], sl[4][64];
+    const int64_t n_valid = hdr->n_valid < row_end ? hdr->n_valid : row_end;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t p = row0 + (int64_t)blockIdx.x * 64 + lane;
+    float M = -__builtin_huge_valf(), L = 0.0f;
+    if (p < n_valid) {
+#pragma unroll 4
+        for (int s = w; s < slots; s += 4) {
+            const float m = pmax[s * slot_stride + p];
+            const float l = psum[s * slot_stride + p];
+            if (m > -__builtin_huge_valf()) {
+                const float Mn = fmaxf(M, m);
+                L = L * __expf(M - Mn) + l * __expf(m - Mn);
+                M = Mn;
+            }
+        }
+    }
+    sm[w][lane] = M;
+    sl[w][lane] = L;
+    __syncthreads();
+    if (w == 0 && p < n_valid) {
+        float Mt = fmaxf(fmaxf(sm[0][lane], sm[1][lane]), fmaxf(sm[2][lane], sm[3][lane]));
+        float Lt = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (sm[i][lane] > -__builtin_huge_valf()) Lt += sl[i][lane] * expf(sm[i][lane] - Mt);
+        lse_out[p] = Mt + logf(Lt);
+    }
+}
+
+// Per valid token: the surrogate of
 // Sec. 3.2: rho = exp(logp - old_logp), min[rho a, clip(rho, 1-eps, 1+eps) a], its weight
 // 1/(R len_i), and g = d loss / d logp; with a reference policy, minus kl_coef times the per-token
 // KL estimator (Table 2 lists the coefficient).  Block partial sums of the loss in double.
 __global__ __launch_bounds__(256) void surrogate_kernel(
     LossHeader* __restrict__ hdr, const int32_t* __restrict__ row_map,
-    const float* __restrict__ pmax, const float* __restrict__ psum, int slots, int64_t slot_stride,
-    const float* __restrict__ zy, const float* __restrict__ old_logp, const float* __restrict__ ref_logp,
+    const float* __restrict__ lse_in, const float* __restrict__ zy, const float* __restrict__ old_logp, const float* __restrict__ ref_logp,
     float kl_coef, const float* __restrict__ adv,
     const int32_t* __restrict__ lengths, int R, int T, float clip_eps, float grad_scale,
-    float* __restrict__ lse_out, float* __restrict__ g_out, float* __restrict__ coef_out,
-    float* __restrict__ logp_out, double* __restrict__ loss_part) {
+    float* __restrict__ g_out, float* __restrict__ coef_out,
+    float* __restrict__ logp_out, double* __restrict__ loss_part, int64_t row0, int64_t row_end,
+    uint32_t* __restrict__ gmax_block) {
     __shared__ double red[4];
     __shared__ float redg[4];
     __shared__ int redc[4];
-    const int n_valid = hdr->n_valid;
-    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t n_valid = hdr->n_valid < row_end ? hdr->n_valid : row_end;
+    const int64_t p = row0 + (int64_t)blockIdx.x * 256 + threadIdx.x;
     double contrib = 0.0;
     float gabs = 0.0f;
     bool cut = false;
     if (p < n_valid) {
-        float M = -__builtin_huge_valf();
-        for (int s = 0; s < slots; ++s) M = fmaxf(M, pmax[s * slot_stride + p]);
-        float L = 0.0f;
-        for (int s = 0; s < slots; ++s) {
-            const float ms = pmax[s * slot_stride + p];
-            if (ms > -__builtin_huge_valf()) L += psum[s * slot_stride + p] * expf(ms - M);
-        }
-        const float lse = M + logf(L);
+        const float lse = lse_in[p];
         const int flat = row_map[p];
         const int i = flat / T;
         const int len = rollout_len(lengths, i, T);
@@ -241,7 +249,6 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
             dobj += kl_coef * em1;
         }
         const float gp = -c * dobj * grad_scale;
-        lse_out[p] = lse;
         g_out[p] = gp;
         coef_out[p] = gp * -expm1f(logp);  // d loss / d z_y = g (1 - softmax_y)
         gabs = fabsf(gp);
@@ -261,11 +268,14 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        loss_part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+        loss_part[row0 / 256 + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
         const int nc = redc[0] + redc[1] + redc[2] + redc[3];
         if (nc > 0) atomicAdd(&hdr->clipped, nc);   // an integer count: order-independent
         const float gm = fmaxf(fmaxf(redg[0], redg[1]), fmaxf(redg[2], redg[3]));
-        if (gm > 0.0f) atomicMax(&hdr->gmax_bits, __float_as_uint(gm));  // a max: order-independent
+        if (gm > 0.0f) {   // maxima: order-independent
+            atomicMax(gmax_block, __float_as_uint(gm));
+            atomicMax(&hdr->gmax_bits, __float_as_uint(gm));
+        }
     }
 }
 
@@ -285,6 +295,24 @@ __global__ __launch_bounds__(1024) void finalize_loss_kernel(const double* __res
 
 }  // namespace
 
+pods_status launch_surrogate(const LossArgs& a, const LossPlan& p, int64_t row0, int64_t nrows, int block) {
+    unsigned char* ws = a.workspace;
+    PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel, dim3((unsigned)ceil_div(nrows, 64)), dim3(256), 0, a.stream,
+                reinterpret_cast<const LossHeader*>(ws + p.off_hdr), reinterpret_cast<const float*>(ws + p.off_pmax),
+                reinterpret_cast<const float*>(ws + p.off_psum), p.slots, p.ncap_ld, row0, row0 + nrows,
+                reinterpret_cast<float*>(ws + p.off_lse));
+    pods_status st = check_launch("log-sum-exp");
+    if (st != PODS_OK) return st;
+    PODS_LAUNCH("surrogate", a.stream, surrogate_kernel, dim3((unsigned)ceil_div(nrows, 256)), dim3(256), 0, a.stream,
+                reinterpret_cast<LossHeader*>(ws + p.off_hdr), reinterpret_cast<const int32_t*>(ws + p.off_rowmap),
+                reinterpret_cast<const float*>(ws + p.off_lse), reinterpret_cast<const float*>(ws + p.off_zy), a.old_logp, a.ref_logp, a.kl_coef,
+                a.adv, a.lengths, a.R, a.T, a.clip_eps, a.grad_scale,
+                reinterpret_cast<float*>(ws + p.off_g), reinterpret_cast<float*>(ws + p.off_coef), a.logp_out,
+                reinterpret_cast<double*>(ws + p.off_losspart), row0, row0 + nrows,
+                reinterpret_cast<uint32_t*>(ws + p.off_gmax) + block);
+    return check_launch("surrogate");
+}
+
 pods_status run_loss(const LossArgs& a) {
     const LossPlan p = plan_loss(a.R, a.T, a.d, a.V, a.dt, a.workspace_bytes);
     if (p.total > a.workspace_bytes)
@@ -295,17 +323,12 @@ pods_status run_loss(const LossArgs& a) {
     auto* offsets = reinterpret_cast<int32_t*>(ws + p.off_offsets);
     auto* row_map = reinterpret_cast<int32_t*>(ws + p.off_rowmap);
     auto* tok = reinterpret_cast<int32_t*>(ws + p.off_tok);
-    auto* lse = reinterpret_cast<float*>(ws + p.off_lse);
-    auto* zy = reinterpret_cast<float*>(ws + p.off_zy);
-    auto* g = reinterpret_cast<float*>(ws + p.off_g);
-    auto* coef = reinterpret_cast<float*>(ws + p.off_coef);
-    auto* pmax = reinterpret_cast<float*>(ws + p.off_pmax);
-    auto* psum = reinterpret_cast<float*>(ws + p.off_psum);
     auto* loss_part = reinterpret_cast<double*>(ws + p.off_losspart);
     pods_status st;
 
     PODS_LAUNCH("scan_lengths", a.stream, scan_lengths_kernel, dim3(1), dim3(1024), 0, a.stream, a.lengths, a.adv,
-                       a.skip_zero_adv ? 1 : 0, a.R, a.T, offsets, hdr);
+                a.skip_zero_adv ? 1 : 0, a.R, a.T, offsets, reinterpret_cast<uint32_t*>(ws + p.off_gmax),
+                (int)(p.ncap_ld / kTile), hdr);
     if ((st = check_launch("scan_lengths")) != PODS_OK) return st;
     PODS_LAUNCH("fill_rows", a.stream, fill_rows_kernel, dim3((unsigned)a.R, (unsigned)ceil_div(a.T, 256)), dim3(256),
                        0, a.stream, hdr, a.lengths, a.tokens, offsets, a.T, a.V, row_map, tok, a.logp_out);
@@ -316,18 +339,16 @@ pods_status run_loss(const LossArgs& a) {
         if ((st = check_launch("zero_pad_rows")) != PODS_OK) return st;
     }
 
-    st = p.mfma ? mfma_forward(a, p) : simple_forward(a, p);
-    if (st != PODS_OK) return st;
-
-    PODS_LAUNCH("surrogate", a.stream, surrogate_kernel, dim3((unsigned)p.loss_blocks), dim3(256), 0, a.stream, hdr,
-                       row_map, pmax, psum, p.slots, p.ncap_ld, zy, a.old_logp, a.ref_logp, a.kl_coef, a.adv, a.lengths, a.R,
-                       a.T, a.clip_eps, a.grad_scale, lse, g, coef, a.logp_out, loss_part);
-    if ((st = check_launch("surrogate")) != PODS_OK) return st;
+    if (p.mfma) {
+        if ((st = mfma_forward_backward(a, p)) != PODS_OK) return st;
+    } else {
+        if ((st = simple_forward(a, p)) != PODS_OK) return st;
+        if ((st = launch_surrogate(a, p, 0, p.ncap_ld, 0)) != PODS_OK) return st;
+        if ((st = simple_backward(a, p)) != PODS_OK) return st;
+    }
     PODS_LAUNCH("finalize_loss", a.stream, finalize_loss_kernel, dim3(1), dim3(1024), 0, a.stream, loss_part,
                        p.loss_blocks, a.loss);
-    if ((st = check_launch("finalize_loss")) != PODS_OK) return st;
-
-    return p.mfma ? mfma_backward(a, p) : simple_backward(a, p);
+    return check_launch("finalize_loss");
 }
 
 }  // namespace pods

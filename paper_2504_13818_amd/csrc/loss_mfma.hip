@@ -1,14 +1,22 @@
 // Matrix-core kernels for the GRPO-PODS token loss with bf16 inputs (gfx950).
 //
-// All four contractions of the update run as one workgroup per 256x256 output tile with fp32
-// accumulators: the logits with v_mfma_f32_32x32x16_bf16 on transposed copies of the bf16 inputs, the two
-// gradient contractions with v_mfma_f32_32x32x16_f16 on fp16 working copies (exact while the scaled
-// value stays in fp16's normal range):
+// The packed token rows are processed in blocks of nb rows (32768 by default).  Per block, three
+// contractions run as one workgroup per 256x256 output tile with fp32 accumulators: the logits with
+// v_mfma_f32_32x32x16_bf16 on transposed copies of the bf16 inputs, the two gradient contractions with
+// v_mfma_f32_32x32x16_f16 on fp16 working copies (exact while the scaled value stays in fp16's normal
+// range):
 //
-//   forward    z[v][t]  = sum_k Wt[k][v]  Ht[k][t]      -> (max, sum exp) per token and vocabulary tile, z_y
-//   recompute  z[v][t]  (same)                          -> q = 2^14 exp(z - lse) as fp16 (0 at v = y)
-//   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times -g_t, accumulated over vocab chunks
-//   d_w_lm     dW[k][v] = sum_t H16[t][k] q[t][v]       -> complete per vocabulary chunk
+//   forward    z[v][t]  = sum_k Wt[k][v]  Ht[k][t]      -> per token and vocabulary tile: m = max z, sum exp(z - m),
+//                                                          z_y, and the numerators 2^14 exp(z - m) as fp16
+//   rescale    q[t][v]  = numerator * exp(m - lse_t)    -> q = 2^14 softmax (0 at v = y), in place
+//   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times -g_t, over the whole vocabulary
+//   d_w_lm     dW[k][v] = sum_t H16[t][k] q[t][v]       -> accumulated over the token blocks
+//
+// The softmax numerators of ONE token block, q[nb][V], are the only [tokens, vocabulary]-shaped array that
+// ever exists (10 GB of the 90 GB the full logits would take at the Qwen2.5-3B-shaped sizes): keeping them
+// from the forward pass, under a per-tile offset that a cheap elementwise pass corrects once the
+// log-sum-exp is known, spares the backward pass a second logits contraction (2 N d V of the 8 N d V
+// floating-point operations a recomputing backward pass executes).
 //
 // An operand whose contraction index is its row index in memory (all of them except q in
 // d_hidden) is staged in LDS as it lies in memory and read with the transposing LDS load, so q is
@@ -18,8 +26,8 @@
 // The per-logit gradient is dz = -g_t q / 2^14 for v != y.  q is kept in fp16 (11-bit significand)
 // rather than bf16 (8-bit) so that a logit with a large probability does not carry a 2^-8 error
 // into its token's gradient.  The token weight g_t, which spans many binades, never enters q:
-// d_hidden applies it per output row, and d_w_lm folds it into H16 = fp16(g_t h_t 2^-e) with one
-// global power-of-two range scale.  W16 = fp16(256 W) is an exact copy of the bf16 weight.
+// d_hidden applies it per output row, and d_w_lm folds it into H16 = fp16(s g_t h_t) with one
+// power-of-two range scale per token block.  W16 = fp16(s_w W) is an exact copy of the bf16 weight.
 // The generated token's own logit, dz_y = g (1 - softmax_y), dominates each token's gradient and
 // is kept out of the rounded operands altogether: its two rank-one terms, dz_y W_y into d_hidden
 // and dz_y h_t into row y of d_w_lm, are added in fp32 by two small kernels (exact bf16 products,
@@ -54,7 +62,8 @@ constexpr int kStages = 4;                         // ring of LDS stages
 constexpr int kDist = kStages - 1;                 // k-tiles in flight ahead of the one being multiplied
 constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
 constexpr int kQPitch = 2 * kTile + 8;             // bytes per token row of the q tile staged in LDS
-constexpr int kRecomputeLdsBytes = kTile * kQPitch > kLdsBytes ? kTile * kQPitch : kLdsBytes;   // 130 KiB
+constexpr int kStatsOffset = kTile * kQPitch > kLdsBytes ? kTile * kQPitch : kLdsBytes;   // past the staged q tile
+constexpr int kFwdLdsBytes = kStatsOffset + 2 * 2 * kTile * 4;   // + [2][256] maxima and [2][256] sums: 134 KiB
 constexpr int kHPitch = 4 * kTile + 16;            // bytes per token row of the d_hidden half-tile staged in LDS
 constexpr int kDhLdsBytes = 128 * kHPitch > kLdsBytes ? 128 * kHPitch : kLdsBytes;   // 130 KiB
 constexpr float kLog2e = 1.4426950408889634f;
@@ -337,148 +346,54 @@ __device__ __forceinline__ int acc_slot_of(int rel) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Forward: one workgroup per (token tile, vocabulary tile): (max, sum exp) of its 256 logits per
-// token, one partial per vocabulary tile, merged later by the surrogate kernel; and z_y.
+// Forward: one workgroup per (token tile, vocabulary tile).  Per token: m = the tile's largest logit,
+// the sum of exp(z - m) over the tile (one partial per vocabulary tile, merged later by the surrogate
+// kernel), z_y, and the tile's softmax numerators 2^14 exp(z - m) rounded to fp16 (0 at v = y and past V),
+// token-major, into the block's q array.  m is common to the tile's two vocabulary waves (exchanged through
+// LDS), so that one factor exp(m - lse) per (token, vocabulary tile) later turns the numerators into
+// 2^14 softmax.
 // One tile per workgroup (rather than a workgroup walking many vocabulary tiles) keeps the 32
 // workgroups of an XCD in step, which is what lets them share operand tiles in the 4 MiB L2.
-// A launch covers vocabulary tiles vt0 .. vt0 + nvt_launch - 1.
+// A launch covers the token tiles of one token block (first row row0) and vocabulary tiles
+// vt0 .. vt0 + nvt_launch - 1.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restrict__ hdr,
-                                                     const int32_t* __restrict__ tok,
-                                                     const uint16_t* __restrict__ ht,
-                                                     const uint16_t* __restrict__ wt,
-                                                     int d, int V, int vt0, int nvt_launch,
-                                                     int ntt_grid, int64_t slot_stride,
-                                                     float* __restrict__ pmax, float* __restrict__ psum,
-                                                     float* __restrict__ zy) {
-    extern __shared__ __align__(16) unsigned char lds[];
-    const int n_valid = hdr->n_valid;
-    const int64_t ntt = (n_valid + kTile - 1) / kTile;
-    int64_t tt, vt;
-    if (!decode_tile(blockIdx.x, ntt_grid, nvt_launch, tt, vt) || tt >= ntt) return;
-    vt += vt0;
-    const LaneGeom g = lane_geom();
-    const int KT = d / kBK;
-
-    Operand A, B;
-    operand_kmajor(A, wt + vt * d * kTile, kTile, 0, 0, kTile);
-    operand_kmajor(B, ht + tt * d * kTile, kTile, 0, 0, kTile);
-    f32x16 acc[4][4];
-    zero_acc(acc);
-    k_loop<bf16x8, true, true>(A, B, KT, lds, g, acc);
-
-    const int vbase = (int)vt * kTile + g.wm * 128 + 4 * (g.lane >> 5);  // row of (mi=0, r=0)
-    const bool partial = (int)vt * kTile + kTile > V;   // last vocabulary tile: rows >= V do not exist
-    float* red = reinterpret_cast<float*>(lds);   // [256 tokens][2]: wm = 1 hands its partials to wm = 0
-    float Mv[4], Sv[4];
-    __builtin_amdgcn_s_barrier();                 // every wave has left the ring
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-        const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
-        const int64_t p = tt * kTile + tloc;
-        const int y = (p < n_valid) ? tok[p] : -1;
-        float val[4][16];
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) val[mi][r] = acc[mi][ni][r];
-        if (partial) {
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (vbase + mi * 32 + 8 * (r >> 2) + (r & 3) >= V) val[mi][r] = -__builtin_huge_valf();
-        }
-        // z_y lives in exactly one lane of one wave of one vocabulary tile
-        const int slot = acc_slot_of(y - vbase);
-        if (__any(slot >= 0)) {
-            float zv = 0.0f;
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (slot == mi * 16 + r) zv = val[mi][r];
-            if (slot >= 0) zy[p] = zv;
-        }
-        float m = val[0][0];
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) m = fmaxf(m, val[mi][r]);
-        m = fmaxf(m, __shfl_xor(m, 32, 64));          // lanes l and l^32: same token, other rows
-        const float M = m;           // accumulators hold kLogitScale * z
-        const float Ms = (M == -__builtin_huge_valf()) ? 0.0f : M;
-        const float off = -Ms * kLog2e;
-        float sum = 0.0f;
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                sum += __builtin_amdgcn_exp2f(fmaf(val[mi][r], kLog2e, off));
-        sum += __shfl_xor(sum, 32, 64);
-        if (g.wm == 1 && g.lane < 32) {
-            red[tloc * 2] = M;
-            red[tloc * 2 + 1] = sum;
-        }
-        Mv[ni] = M;
-        Sv[ni] = sum;
-        __builtin_amdgcn_sched_barrier(0);   // one token column at a time: keeps the accumulator copies few
-    }
-    __syncthreads();
-    if (g.wm == 0 && g.lane < 32) {
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const int tloc = g.wn * 128 + ni * 32 + g.lane;
-            const int64_t p = tt * kTile + tloc;
-            const float M1 = red[tloc * 2], S1 = red[tloc * 2 + 1];
-            const float Mn = fmaxf(Mv[ni], M1);
-            float St = 0.0f;
-            if (Mn > -__builtin_huge_valf())
-                St = Sv[ni] * __builtin_amdgcn_exp2f((Mv[ni] - Mn) * kLog2e) + S1 * __builtin_amdgcn_exp2f((M1 - Mn) * kLog2e);
-            if (p < n_valid) {
-                pmax[vt * slot_stride + p] = Mn;
-                psum[vt * slot_stride + p] = St;
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// Backward step 1 (per vocabulary chunk): recompute the logits tile and form
-// q = kQScale exp(z - lse), rounded to fp16, 0 at v = y, token-major (dz = -g q / kQScale).
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 1) void recompute_kernel(
-    const LossHeader* __restrict__ hdr, const int32_t* __restrict__ tok,
-    const float* __restrict__ lse, const uint16_t* __restrict__ ht,
-    const uint16_t* __restrict__ wt, int d, int V, int v0, int vc, int ntt_grid, int64_t ldq,
-    _Float16* __restrict__ q) {
-    extern __shared__ __align__(16) unsigned char lds[];
-    const int n_valid = hdr->n_bwd;
-    const int64_t ntt = (n_valid + kTile - 1) / kTile;
-    int64_t tt, vt;
-    if (!decode_tile(blockIdx.x, ntt_grid, vc / kTile, tt, vt) || tt >= ntt) return;
-    if ((int64_t)v0 + vt * kTile >= V) return;   // past the vocabulary: the gradient kernels stop there too
-    const LaneGeom g = lane_geom();
-    const int KT = d / kBK;
-
-    Operand A, B;
-    operand_kmajor(A, wt + ((int64_t)v0 / kTile + vt) * d * kTile, kTile, 0, 0, kTile);
-    operand_kmajor(B, ht + tt * d * kTile, kTile, 0, 0, kTile);
-    f32x16 acc[4][4];
-    zero_acc(acc);
-    k_loop<bf16x8, true, true>(A, B, KT, lds, g, acc);
-
+template <bool PARTIAL>
+__device__ __forceinline__ void fwd_epilogue(const f32x16 (&acc)[4][4], const LaneGeom& g, unsigned char* lds,
+                                             const int32_t* __restrict__ tok, int64_t n_valid, int64_t gt,
+                                             int64_t vt, int V, int64_t slot_stride, float* __restrict__ pmax,
+                                             float* __restrict__ psum, float* __restrict__ zy,
+                                             _Float16* __restrict__ qtile, int64_t ldq) {
     const int vtile = g.wm * 128 + 4 * (g.lane >> 5);        // tile-local vocabulary row of (mi=0, r=0)
-    const int vbase = v0 + (int)vt * kTile + vtile;
-    const bool partial = (v0 + (int)vt * kTile + kTile > V);
+    const int vbase = (int)vt * kTile + vtile;
+    const int vlimit = V - vbase;                            // rows at or past this offset do not exist
+    float* red_max = reinterpret_cast<float*>(lds + kStatsOffset);   // [2 vocabulary waves][256 tokens]
+    float* red_sum = red_max + 2 * kTile;
     constexpr float kLog2Q = 14.0f;
     static_assert(kQScale == 16384.0f, "kLog2Q must be log2(kQScale)");
+    float Mt[4], S[4];
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+        float m = -__builtin_huge_valf();
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (PARTIAL && mi * 32 + 8 * (r >> 2) + (r & 3) >= vlimit) continue;
+                m = fmaxf(m, acc[mi][ni][r]);
+            }
+        m = fmaxf(m, __shfl_xor(m, 32, 64));          // lanes l and l^32: same token, other rows
+        Mt[ni] = m;
+        if (g.lane < 32) red_max[g.wm * kTile + g.wn * 128 + ni * 32 + g.lane] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni)   // the tile holds at least one vocabulary row, so this is finite
+        Mt[ni] = fmaxf(Mt[ni], red_max[(g.wm ^ 1) * kTile + g.wn * 128 + ni * 32 + (g.lane & 31)]);
+
     // The q tile goes to memory through LDS: a lane holds 4 consecutive vocabulary entries of one token,
     // so storing from registers would scatter 8-byte pieces over 32 token rows per instruction; staged
     // as [token][vocabulary] rows (pitch 520 B: the 32 rows a half-wave writes fall into 32 different
     // bank pairs) every later store instruction covers two whole 512-byte rows.
-    __builtin_amdgcn_s_barrier();   // every wave has left the operand ring
-    _Float16* qtile = q + (tt * kTile) * ldq + vt * kTile;
     // Two passes over the tile's tokens (MFMA block columns 0-1, then 2-3 of each wave): the stores of the
     // first pass drain while the second pass computes its exponentials.
 #pragma unroll
@@ -487,42 +402,44 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
         for (int nj = 0; nj < 2; ++nj) {
             const int ni = 2 * pass + nj;
             const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
-            const int64_t p = tt * kTile + tloc;
+            const int64_t p = gt * kTile + tloc;
             const bool valid = p < n_valid;
-            const int y = valid ? tok[p] : -1;
-            // kQScale softmax = 2^(z log2e - lse log2e + 14); rows past N get 2^-inf = 0
-            const float off = valid ? fmaf(-lse[p], kLog2e, kLog2Q) : -__builtin_huge_valf();
-            float val[4][16];
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    val[mi][r] = __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][r], kLog2e, off));
-            const int slot = acc_slot_of(y - vbase);
-            if (__any(slot >= 0)) {
-#pragma unroll
-                for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (slot == mi * 16 + r) val[mi][r] = 0.0f;  // the y logit is handled in fp32
-            }
-            if (partial) {
-#pragma unroll
-                for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (vbase + mi * 32 + 8 * (r >> 2) + (r & 3) >= V) val[mi][r] = 0.0f;
-            }
+            // kQScale exp(z - m) = 2^(z log2e - m log2e + 14); rows past N get 2^-inf = 0
+            const float off = valid ? fmaf(-Mt[ni], kLog2e, kLog2Q) : -__builtin_huge_valf();
             unsigned char* row = lds + tloc * kQPitch + vtile * 2;
+            float sum = 0.0f;
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     f16x4 pk;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) pk[c] = (_Float16)val[mi][b * 4 + c];
+                    for (int c = 0; c < 4; ++c) {
+                        float e = __builtin_amdgcn_exp2f(fmaf(acc[mi][ni][b * 4 + c], kLog2e, off));
+                        if (PARTIAL && mi * 32 + 8 * b + c >= vlimit) e = 0.0f;
+                        sum += e;
+                        pk[c] = (_Float16)e;
+                    }
                     *reinterpret_cast<f16x4*>(row + (mi * 32 + 8 * b) * 2) = pk;
                 }
+            sum += __shfl_xor(sum, 32, 64);
+            S[ni] = sum;
+            // z_y lives in exactly one lane of one wave of one vocabulary tile; its numerator stays in the
+            // sum and leaves q (the y logit's gradient is applied in fp32)
+            const int y = valid ? tok[p] : -1;
+            const int slot = acc_slot_of(y - vbase);
+            if (__any(slot >= 0)) {
+                float zv = 0.0f;
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (slot == mi * 16 + r) zv = acc[mi][ni][r];
+                if (slot >= 0) {
+                    zy[p] = zv;
+                    *reinterpret_cast<_Float16*>(row + (y - vbase) * 2) = (_Float16)0.0f;
+                }
+            }
         }
         __syncthreads();
         // this pass filled token rows 128 h + 64 pass .. + 63 (h = 0, 1); wave w stores 32 of them, two rows
@@ -537,32 +454,107 @@ __global__ __launch_bounds__(256, 1) void recompute_kernel(
             *reinterpret_cast<f16x8*>(qtile + (int64_t)r * ldq + (g.lane & 31) * 8) = both;
         }
     }
+    if (g.wm == 1 && g.lane < 32) {
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) red_sum[g.wn * 128 + ni * 32 + g.lane] = S[ni];
+    }
+    __syncthreads();
+    if (g.wm == 0 && g.lane < 32) {
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            const int tloc = g.wn * 128 + ni * 32 + g.lane;
+            const int64_t p = gt * kTile + tloc;
+            if (p < n_valid) {
+                pmax[vt * slot_stride + p] = Mt[ni];
+                psum[vt * slot_stride + p] = (S[ni] + red_sum[tloc]) * (1.0f / kQScale);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restrict__ hdr,
+                                                     const int32_t* __restrict__ tok,
+                                                     const uint16_t* __restrict__ ht,
+                                                     const uint16_t* __restrict__ wt,
+                                                     int d, int V, int vt0, int nvt_launch, int64_t row0,
+                                                     int ntt_grid, int64_t slot_stride,
+                                                     float* __restrict__ pmax, float* __restrict__ psum,
+                                                     float* __restrict__ zy, int64_t ldq,
+                                                     _Float16* __restrict__ q) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int64_t n_valid = hdr->n_valid;
+    int64_t tt, vt;
+    if (!decode_tile(blockIdx.x, ntt_grid, nvt_launch, tt, vt)) return;
+    const int64_t gt = row0 / kTile + tt;         // token tile among all packed rows
+    if (gt * kTile >= n_valid) return;
+    vt += vt0;
+    const LaneGeom g = lane_geom();
+    const int KT = d / kBK;
+
+    Operand A, B;
+    operand_kmajor(A, wt + vt * d * kTile, kTile, 0, 0, kTile);
+    operand_kmajor(B, ht + gt * d * kTile, kTile, 0, 0, kTile);
+    f32x16 acc[4][4];
+    zero_acc(acc);
+    k_loop<bf16x8, true, true>(A, B, KT, lds, g, acc);
+
+    __builtin_amdgcn_s_barrier();                 // every wave has left the operand ring
+    _Float16* qtile = q + (tt * kTile) * ldq + vt * kTile;
+    if ((int)vt * kTile + kTile > V)              // last vocabulary tile: rows >= V do not exist
+        fwd_epilogue<true>(acc, g, lds, tok, n_valid, gt, vt, V, slot_stride, pmax, psum, zy, qtile, ldq);
+    else
+        fwd_epilogue<false>(acc, g, lds, tok, n_valid, gt, vt, V, slot_stride, pmax, psum, zy, qtile, ldq);
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward step 2: d_hidden[t][k] -= (g_t / (kQScale s_w)) sum_{v in chunk} q[t][v] W16[v][k], W16 = s_w W
-// (the rows were initialised with the y-logit term)
+// Rescale (per token block, once its log-sum-exp is known): numerators -> q = 2^14 softmax, in place.
+// One factor exp(m - lse) per (token, vocabulary tile); 16 bytes per lane.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rescale_kernel(const LossHeader* __restrict__ hdr,
+                                                      const float* __restrict__ lse,
+                                                      const float* __restrict__ pmax, int64_t slot_stride,
+                                                      int64_t row0, int granules, int64_t ldq,
+                                                      _Float16* __restrict__ q) {
+    const int64_t r = blockIdx.y;
+    const int64_t p = row0 + r;
+    if (p >= hdr->n_bwd) return;
+    const int gcol = blockIdx.x * 256 + threadIdx.x;
+    if (gcol >= granules) return;
+    const int vt = gcol >> 5;                    // 32 granules of 8 per vocabulary tile
+    const float s = __expf(pmax[vt * slot_stride + p] - lse[p]);   // <= 1: m is one of the terms of lse
+    _Float16* at = q + r * ldq + (int64_t)gcol * 8;
+    f16x8 x = *reinterpret_cast<const f16x8*>(at);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = (_Float16)((float)x[j] * s);
+    *reinterpret_cast<f16x8*>(at) = x;
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward: d_hidden[t][k] -= (g_t / (kQScale s_w)) sum_v q[t][v] W16[v][k], W16 = s_w W, over the whole
+// vocabulary, for the token tiles of one token block (the rows were initialised with the y-logit term)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict__ hdr,
                                                     const int32_t* __restrict__ row_map,
                                                     const float* __restrict__ gvec,
                                                     const uint16_t* __restrict__ w16,
                                                     const uint16_t* __restrict__ q, int64_t ldq, int d,
-                                                    int V, int v0, int vc, int ntt_grid, float* __restrict__ d_hidden) {
+                                                    int V, int64_t row0, int ntt_grid,
+                                                    float* __restrict__ d_hidden) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const int n_valid = hdr->n_bwd;
-    const int64_t ntt = (n_valid + kTile - 1) / kTile;
-    int64_t tt, kt0;
-    if (!decode_tile(blockIdx.x, ntt_grid, (d + kTile - 1) / kTile, tt, kt0) || tt >= ntt) return;
+    const int64_t n_valid = hdr->n_bwd;
+    int64_t tb, kt0;      // token tile within the block, d-tile
+    if (!decode_tile(blockIdx.x, ntt_grid, (d + kTile - 1) / kTile, tb, kt0)) return;
+    const int64_t tt = row0 / kTile + tb;             // token tile among all packed rows
+    if (tt * kTile >= n_valid) return;
     const LaneGeom g = lane_geom();
 
     Operand A, B;
-    operand_kmajor(A, w16, d, v0, kt0 * kTile, d);   // rows v >= V of W16 are zero
-    // every row of the last token tile was written by the recompute step (zeros past N)
-    operand_rows(B, q, ldq, tt * kTile, ntt * kTile, 0);
+    operand_kmajor(A, w16, d, 0, kt0 * kTile, d);    // rows v >= V of W16 are zero
+    // every row of a token tile that holds a valid row was written by the forward step (zeros past N)
+    operand_rows(B, q, ldq, tb * kTile, (tb + 1) * kTile, 0);
     f32x16 acc[4][4];
     zero_acc(acc);
-    const int vwidth = min(vc, (V - v0 + kTile - 1) / kTile * kTile);   // whole tiles that hold vocabulary
+    const int vwidth = (V + kTile - 1) / kTile * kTile;   // whole tiles that hold vocabulary
     k_loop<f16x8, true, false>(A, B, vwidth / kBK, lds, g, acc);
 
     // The tile is added to d_hidden through LDS, half of its tokens at a time: a lane holds 4 consecutive
@@ -632,34 +624,38 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward step 3: d_w_lm[v][k] = -(1 / (kQScale s)) sum_t q[t][v] H16[t][k], H16 = g_t h_t s
-// (all tokens: complete per chunk)
+// Backward: d_w_lm[v][k] (+)= -(1 / (kQScale s)) sum_{t in block} q[t][v] H16[t][k], H16 = s g_t h_t with the
+// block's range scale s.  The first token block stores (or adds to the caller's array, when accumulating),
+// the later ones add: the blocks are summed in their fixed order.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict__ hdr,
+                                                    const uint32_t* __restrict__ gmax_block,
                                                     const uint16_t* __restrict__ h16,
                                                     const uint16_t* __restrict__ q, int64_t ldq,
-                                                    int d, int V, int v0, int vc, int accumulate,
-                                                    float* __restrict__ d_w) {
+                                                    int d, int V, int64_t row0, int64_t nb, int first_block,
+                                                    int accumulate, float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const int n_valid = hdr->n_bwd;
+    int64_t n_rows = hdr->n_bwd - row0;               // rows of this block that take part
+    n_rows = n_rows < 0 ? 0 : (n_rows > nb ? nb : n_rows);
+    if (n_rows == 0 && !first_block) return;          // nothing to add
+    const int64_t vround = ((int64_t)V + kTile - 1) / kTile * kTile;
     int64_t vt, kt0;
-    if (!decode_tile(blockIdx.x, vc / kTile, (d + kTile - 1) / kTile, vt, kt0)) return;
-    if ((int64_t)v0 + vt * kTile >= V) return;
+    if (!decode_tile(blockIdx.x, vround / kTile, (d + kTile - 1) / kTile, vt, kt0)) return;
     const LaneGeom g = lane_geom();
 
     Operand A, B;
-    // token rows past N (up to the end of the last token tile) are zero in both operands
-    operand_kmajor(A, h16, d, 0, kt0 * kTile, d);
-    operand_kmajor(B, q, ldq, 0, vt * kTile, vc);
+    // token rows past N (up to the end of the last token tile) are zero in H16 and finite in q
+    operand_kmajor(A, h16, d, row0, kt0 * kTile, d);
+    operand_kmajor(B, q, ldq, 0, vt * kTile, vround);
     f32x16 acc[4][4];
     zero_acc(acc);
-    const int KT = (n_valid + kBK - 1) / kBK;
+    const int KT = (int)((n_rows + kBK - 1) / kBK);
     if (KT > 0) k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
-    const float scale = -1.0f / (kQScale * g_range_scale(hdr));
+    const float scale = -1.0f / (kQScale * g_range_scale(*gmax_block, hdr));
 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
-        const int64_t v = (int64_t)v0 + vt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+        const int64_t v = vt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
         if (v >= V) continue;
         float* row = d_w + v * d;
 #pragma unroll
@@ -679,16 +675,16 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
 
 // ------------------------------------------------------------------------------------------
 // The generated token's own logit, in fp32.  coef_t = g_t (1 - softmax_y) = d loss / d z_y.
-//   d_hidden[t][:]  = coef_t W[y_t][:]            (initialises the row; the chunks accumulate on it)
-//   d_w_lm[y_t][:] += coef_t h_t[:]               (after the chunks have stored their rows)
+//   d_hidden[t][:]  = coef_t W[y_t][:]            (initialises the row; the contraction accumulates on it)
+//   d_w_lm[y_t][:] += coef_t h_t[:]               (after the token blocks have stored and added their parts)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void dh_onehot_kernel(const LossHeader* __restrict__ hdr,
                                                         const int32_t* __restrict__ row_map,
                                                         const int32_t* __restrict__ tok,
                                                         const float* __restrict__ coef,
                                                         const uint16_t* __restrict__ w, int d,
-                                                        float* __restrict__ d_hidden) {
-    const int64_t p = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // one wave per token
+                                                        int64_t row0, float* __restrict__ d_hidden) {
+    const int64_t p = row0 + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // one wave per token
     if (p >= hdr->n_bwd) return;
     const int lane = threadIdx.x & 63;
     const float c = coef[p];
@@ -790,7 +786,12 @@ __global__ __launch_bounds__(256) void transpose_kernel(LossHeader* __restrict__
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, off, 64));
-    if (tx == 0 && amax != 0u) atomicMax(token_rows ? &hdr->hmax_bits : &hdr->wmax_bits, amax << 16);
+    if (tx == 0 && amax != 0u) {
+        // a plain look first: after the first few workgroups nearly none still raises the maximum, and
+        // hundreds of thousands of atomics on one address would take longer than the copy itself
+        uint32_t* slot = token_rows ? &hdr->hmax_bits : &hdr->wmax_bits;
+        if ((amax << 16) > *reinterpret_cast<volatile uint32_t*>(slot)) atomicMax(slot, amax << 16);
+    }
     __syncthreads();
     for (int kk = ty; kk < 64; kk += 4) {
         const int64_t r = r0 + tx;
@@ -799,29 +800,34 @@ __global__ __launch_bounds__(256) void transpose_kernel(LossHeader* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------
-// fp16 operand copies (once per call):
-//   W16[v][k] = s_w W[v][k]               (zero rows for v >= V; exact in fp16's normal range: bf16 has
-//                                          fewer significand bits; s_w = the range scale of W)
-//   H16[p][k] = s g_p H[row_map[p]][k]    (zero rows for p >= N up to the end of the last token tile;
-//                                          s = the global range scale of g)
+// fp16 operand copies:
+//   W16[v][k] = s_w W[v][k]               (once per call; zero rows for v >= V; exact in fp16's normal range:
+//                                          bf16 has fewer significand bits; s_w = the range scale of W)
+//   H16[p][k] = s g_p H[row_map[p]][k]    (per token block, rows row0 .. row0 + rows - 1; zero rows for
+//                                          p >= N up to the end of the last token tile; s = the block's
+//                                          range scale of g)
 // One thread per 8 elements.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restrict__ hdr,
+                                                      const uint32_t* __restrict__ gmax_block,
                                                       const int32_t* __restrict__ gather,
                                                       const float* __restrict__ gvec,
-                                                      const uint16_t* __restrict__ src, int64_t rows,
-                                                      int64_t rows_out, int d, int token_rows,
+                                                      const uint16_t* __restrict__ src, int64_t row0,
+                                                      int64_t rows, int64_t rows_valid, int d, int token_rows,
                                                       _Float16* __restrict__ dst) {
-    int64_t nrows = rows, fill_to = rows_out;
-    float common = w_range_scale(hdr);
+    int64_t nrows = rows_valid, fill_to = row0 + rows;
+    float common;
     if (token_rows) {
         nrows = hdr->n_bwd;
-        fill_to = (nrows + kTile - 1) / kTile * kTile;
-        common = g_range_scale(hdr);
+        const int64_t tile_end = (nrows + kTile - 1) / kTile * kTile;
+        fill_to = tile_end < fill_to ? tile_end : fill_to;
+        common = g_range_scale(*gmax_block, hdr);
+    } else {
+        common = w_range_scale(hdr);
     }
     const int per_row = d / 8;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t r = idx / per_row;
+    const int64_t r = row0 + idx / per_row;
     const int k = (int)(idx % per_row) * 8;
     if (r >= fill_to) return;
     f16x8 out;
@@ -848,88 +854,79 @@ pods_status reserve(const void* kernel, const char* what, int bytes = kLdsBytes)
 
 }  // namespace
 
-pods_status mfma_forward(const LossArgs& a, const LossPlan& p) {
+pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
     unsigned char* ws = a.workspace;
     auto* hdr = reinterpret_cast<LossHeader*>(ws + p.off_hdr);
-    auto* row_map = reinterpret_cast<const int32_t*>(ws + p.off_rowmap);
-    auto* wt = reinterpret_cast<uint16_t*>(ws + p.off_wtt);
-    auto* ht = reinterpret_cast<uint16_t*>(ws + p.off_htt);
-    pods_status st = reserve(reinterpret_cast<const void*>(fwd_kernel), "token loss forward");
-    if (st != PODS_OK) return st;
-    const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
-    PODS_LAUNCH("transpose W", a.stream, transpose_kernel, dim3((unsigned)(p.vld_t / 64), dtiles64), dim3(256), 0,
-                a.stream, hdr, nullptr, static_cast<const uint16_t*>(a.w_lm), (int64_t)a.V, a.d, p.vld_t, 0, wt);
-    if ((st = check_launch("transpose W")) != PODS_OK) return st;
-    PODS_LAUNCH("transpose H", a.stream, transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
-                a.stream, hdr, row_map, static_cast<const uint16_t*>(a.hidden), (int64_t)0, a.d, p.ncap_ld, 1, ht);
-    if ((st = check_launch("transpose H")) != PODS_OK) return st;
-    const int64_t ntt = p.ncap_ld / kTile;
-    const int64_t nvt = p.vld_t / kTile;
-    // One launch per kDefaultVocabChunk columns: the chunk of W then stays in the Infinity Cache while the
-    // token tiles stream past it (one launch over the whole vocabulary re-reads W from HBM for every
-    // block of token tiles and measured 6 % slower).
-    const int64_t step_vt = kDefaultVocabChunk / kTile;
-    for (int64_t vt0 = 0; vt0 < nvt; vt0 += step_vt) {
-        const int64_t nl = nvt - vt0 < step_vt ? nvt - vt0 : step_vt;
-        PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nl)), dim3(256),
-                    kLdsBytes, a.stream, hdr, reinterpret_cast<const int32_t*>(ws + p.off_tok),
-                    reinterpret_cast<const uint16_t*>(ht), reinterpret_cast<const uint16_t*>(wt), a.d, a.V, (int)vt0,
-                    (int)nl, (int)ntt, p.ncap_ld, reinterpret_cast<float*>(ws + p.off_pmax),
-                    reinterpret_cast<float*>(ws + p.off_psum), reinterpret_cast<float*>(ws + p.off_zy));
-        if ((st = check_launch("token loss forward")) != PODS_OK) return st;
-    }
-    return PODS_OK;
-}
-
-pods_status mfma_backward(const LossArgs& a, const LossPlan& p) {
-    unsigned char* ws = a.workspace;
-    auto* hdr = reinterpret_cast<const LossHeader*>(ws + p.off_hdr);
+    auto* gmax = reinterpret_cast<const uint32_t*>(ws + p.off_gmax);
     auto* row_map = reinterpret_cast<const int32_t*>(ws + p.off_rowmap);
     auto* tok = reinterpret_cast<const int32_t*>(ws + p.off_tok);
     auto* lse = reinterpret_cast<const float*>(ws + p.off_lse);
     auto* g = reinterpret_cast<const float*>(ws + p.off_g);
     auto* coef = reinterpret_cast<const float*>(ws + p.off_coef);
+    auto* pmax = reinterpret_cast<float*>(ws + p.off_pmax);
+    auto* psum = reinterpret_cast<float*>(ws + p.off_psum);
+    auto* zy = reinterpret_cast<float*>(ws + p.off_zy);
+    auto* wt = reinterpret_cast<uint16_t*>(ws + p.off_wtt);
+    auto* ht = reinterpret_cast<uint16_t*>(ws + p.off_htt);
     auto* w16 = reinterpret_cast<_Float16*>(ws + p.off_wt);
     auto* h16 = reinterpret_cast<_Float16*>(ws + p.off_ht);
-    auto* dz = reinterpret_cast<_Float16*>(ws + p.off_dz);
-    auto* wt = reinterpret_cast<const uint16_t*>(ws + p.off_wtt);
-    auto* ht = reinterpret_cast<const uint16_t*>(ws + p.off_htt);
+    auto* q = reinterpret_cast<_Float16*>(ws + p.off_dz);
     const auto* hidden = static_cast<const uint16_t*>(a.hidden);
     const auto* w = static_cast<const uint16_t*>(a.w_lm);
     pods_status st;
-    if ((st = reserve(reinterpret_cast<const void*>(recompute_kernel), "token loss recompute", kRecomputeLdsBytes)) != PODS_OK) return st;
+    if ((st = reserve(reinterpret_cast<const void*>(fwd_kernel), "token loss forward", kFwdLdsBytes)) != PODS_OK) return st;
     if ((st = reserve(reinterpret_cast<const void*>(dh_kernel), "token loss d_hidden", kDhLdsBytes)) != PODS_OK) return st;
     if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
 
+    // once per call: transposed bf16 copies for the logits (they also find max |W|, max |h|), fp16 copy of W
+    const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
+    PODS_LAUNCH("transpose W", a.stream, transpose_kernel, dim3((unsigned)(p.vld / 64), dtiles64), dim3(256), 0,
+                a.stream, hdr, nullptr, w, (int64_t)a.V, a.d, p.vld, 0, wt);
+    if ((st = check_launch("transpose W")) != PODS_OK) return st;
+    PODS_LAUNCH("transpose H", a.stream, transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
+                a.stream, hdr, row_map, hidden, (int64_t)0, a.d, p.ncap_ld, 1, ht);
+    if ((st = check_launch("transpose H")) != PODS_OK) return st;
     const int64_t per_row = a.d / 8;
     PODS_LAUNCH("convert W", a.stream, convert_kernel, dim3((unsigned)ceil_div(p.vld * per_row, 256)), dim3(256), 0,
-                a.stream, hdr, nullptr, nullptr, w, (int64_t)a.V, p.vld, a.d, 0, w16);
+                a.stream, hdr, nullptr, nullptr, nullptr, w, (int64_t)0, p.vld, (int64_t)a.V, a.d, 0, w16);
     if ((st = check_launch("convert W")) != PODS_OK) return st;
-    PODS_LAUNCH("convert H", a.stream, convert_kernel, dim3((unsigned)ceil_div(p.ncap_ld * per_row, 256)), dim3(256), 0,
-                a.stream, hdr, row_map, g, hidden, (int64_t)0, p.ncap_ld, a.d, 1, h16);
-    if ((st = check_launch("convert H")) != PODS_OK) return st;
 
-    PODS_LAUNCH("token loss d_hidden (y logit)", a.stream, dh_onehot_kernel, dim3((unsigned)ceil_div(p.ncap, 4)), dim3(256), 0, a.stream, hdr,
-                       row_map, tok, coef, w, a.d, a.d_hidden);
-    if ((st = check_launch("token loss d_hidden (y logit)")) != PODS_OK) return st;
-
-    const int64_t ntt = p.ncap_ld / kTile;
+    const int64_t nvt = p.vld / kTile;
     const int64_t dt256 = ceil_div(a.d, kTile);
-    const int64_t vt_chunk = p.vc / kTile;
-    for (int c = 0; c < p.nchunks; ++c) {
-        const int v0 = c * p.vc;
-        if (v0 >= a.V) break;
-        PODS_LAUNCH("token loss recompute", a.stream, recompute_kernel, dim3((unsigned)super_grid_blocks(ntt, vt_chunk)), dim3(256),
-                           kRecomputeLdsBytes, a.stream, hdr, tok, lse, ht, wt, a.d, a.V, v0, p.vc, (int)ntt, p.ldq, dz);
-        if ((st = check_launch("token loss recompute")) != PODS_OK) return st;
-        PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256), kDhLdsBytes,
-                           a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
-                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, (int)ntt, a.d_hidden);
+    const int64_t step_vt = kDefaultVocabChunk / kTile;
+    const int granules = (int)(p.vld / 8);
+    for (int b = 0; b < p.nblocks; ++b) {
+        const int64_t row0 = (int64_t)b * p.nb;
+        const int64_t rows = p.ncap_ld - row0 < p.nb ? p.ncap_ld - row0 : p.nb;   // capacity of this block
+        const int64_t ntt = rows / kTile;
+        // Forward, one launch per kDefaultVocabChunk columns: the chunk of W then stays in the Infinity Cache
+        // while the block's token tiles stream past it.
+        for (int64_t vt0 = 0; vt0 < nvt; vt0 += step_vt) {
+            const int64_t nl = nvt - vt0 < step_vt ? nvt - vt0 : step_vt;
+            PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nl)),
+                        dim3(256), kFwdLdsBytes, a.stream, hdr, tok, reinterpret_cast<const uint16_t*>(ht),
+                        reinterpret_cast<const uint16_t*>(wt), a.d, a.V, (int)vt0, (int)nl, row0, (int)ntt,
+                        p.ncap_ld, pmax, psum, zy, p.ldq, q);
+            if ((st = check_launch("token loss forward")) != PODS_OK) return st;
+        }
+        if ((st = launch_surrogate(a, p, row0, rows, b)) != PODS_OK) return st;
+        PODS_LAUNCH("token loss rescale", a.stream, rescale_kernel, dim3((unsigned)ceil_div(granules, 256), (unsigned)rows),
+                    dim3(256), 0, a.stream, hdr, lse, pmax, p.ncap_ld, row0, granules, p.ldq, q);
+        if ((st = check_launch("token loss rescale")) != PODS_OK) return st;
+        PODS_LAUNCH("convert H", a.stream, convert_kernel, dim3((unsigned)ceil_div(rows * per_row, 256)), dim3(256), 0,
+                    a.stream, hdr, gmax + b, row_map, g, hidden, row0, rows, (int64_t)0, a.d, 1, h16);
+        if ((st = check_launch("convert H")) != PODS_OK) return st;
+        PODS_LAUNCH("token loss d_hidden (y logit)", a.stream, dh_onehot_kernel, dim3((unsigned)ceil_div(rows, 4)),
+                    dim3(256), 0, a.stream, hdr, row_map, tok, coef, w, a.d, row0, a.d_hidden);
+        if ((st = check_launch("token loss d_hidden (y logit)")) != PODS_OK) return st;
+        PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256),
+                    kDhLdsBytes, a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
+                    reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, (int)ntt, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
-        PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(vt_chunk, dt256)), dim3(256),
-                           kLdsBytes, a.stream, hdr, reinterpret_cast<const uint16_t*>(h16),
-                           reinterpret_cast<const uint16_t*>(dz), p.ldq, a.d, a.V, v0, p.vc, a.accumulate_d_w ? 1 : 0,
-                           a.d_w_lm);
+        PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(nvt, dt256)), dim3(256),
+                    kLdsBytes, a.stream, hdr, gmax + b, reinterpret_cast<const uint16_t*>(h16),
+                    reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, rows, b == 0 ? 1 : 0,
+                    (a.accumulate_d_w || b > 0) ? 1 : 0, a.d_w_lm);
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
     }
     PODS_LAUNCH("token loss d_w_lm (y logit)", a.stream, dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,
