@@ -428,6 +428,286 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ r
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Max-variance selection of m = n/4 out of n = 16, 32, ... 256 (the paper's own ratios: 64 -> 16,
+// 32 -> 8, 256 -> 64), with the whole network inside the lanes.
+//
+// Four lanes hold a group, KPL = n/4 keys each, and they sit 16 lanes apart (lanes s, s+16, s+32, s+48:
+// 16 groups per wavefront), because two lane bits at those distances can be exchanged with a register
+// bit by v_permlane16_swap / v_permlane32_swap: one instruction per 32-bit register pair moves the
+// upper half of one register's lanes into the lower half of the other's.  A compare-exchange between
+// two lanes then becomes: transpose (one swap per key word), compare-exchange between two registers of
+// the same lane.  Each lane first sorts its KPL keys with Batcher's odd-even merge sort (543
+// compare-exchanges for 64 keys against 672 of the bitonic network), then two bitonic merges (2 KPL,
+// 4 KPL) run on element-index bits that are register bits when their turn comes; the bit parked in the
+// lane meanwhile is one whose turn is far off, so a merge costs two or three transpositions, not one
+// per stage.
+// Direction: every compare-exchange is ascending in the value as stored.  A run that must descend for
+// the next merge is sorted ascending on negated keys and then has its sign flipped (one XOR per key):
+// these keys are doubles in [2, 4), never zero, so negation reverses their order exactly.
+// After the first two stages of the last merge the lowest and the highest quarter are separated from
+// the middle half, which Theorem 1 never reads: the registers of the middle half are dropped, and the
+// remaining stages run on half the keys.
+// The last transpositions leave lane L = 0..3 of the group with sorted positions [L n/16, (L+1) n/16) of
+// the lowest quarter and the same offsets of the highest quarter in registers, which is exactly the
+// block of candidate splits k a lane scores (split k drops the low position m-k and adds the high
+// position n-k): prefix sums, scores and the emitted indices never leave the registers; no LDS.
+// ------------------------------------------------------------------------------------------------
+template <int WHICH>   // 0: the lane bit 16 apart, 1: the lane bit 32 apart
+__device__ __forceinline__ void lane_reg_swap(double& a, double& b) {
+    unsigned alo = (unsigned)__double2loint(a), ahi = (unsigned)__double2hiint(a);
+    unsigned blo = (unsigned)__double2loint(b), bhi = (unsigned)__double2hiint(b);
+    if constexpr (WHICH == 0) {
+        const auto lo = __builtin_amdgcn_permlane16_swap(alo, blo, false, false);
+        const auto hi = __builtin_amdgcn_permlane16_swap(ahi, bhi, false, false);
+        alo = lo[0]; blo = lo[1]; ahi = hi[0]; bhi = hi[1];
+    } else {
+        const auto lo = __builtin_amdgcn_permlane32_swap(alo, blo, false, false);
+        const auto hi = __builtin_amdgcn_permlane32_swap(ahi, bhi, false, false);
+        alo = lo[0]; blo = lo[1]; ahi = hi[0]; bhi = hi[1];
+    }
+    a = __hiloint2double((int)ahi, (int)alo);
+    b = __hiloint2double((int)bhi, (int)blo);
+}
+
+// Exchange of the element-index bit held by a lane bit with the one held by register bit RB, over the
+// registers for which live(r) holds: afterwards key[r | 1<<RB] of a lane whose bit is 0 holds what
+// key[r] of the partner lane (bit 1) held, and vice versa.
+template <int KPL, int WHICH, int RB, typename Live>
+__device__ __forceinline__ void transpose_bit(double (&key)[KPL], Live live) {
+#pragma unroll
+    for (int r = 0; r < KPL; ++r)
+        if ((r & (1 << RB)) == 0 && live(r)) lane_reg_swap<WHICH>(key[r], key[r | (1 << RB)]);
+}
+// Compare-exchange along register bit RB: the register with the bit clear keeps the smaller key.
+template <int KPL, int RB, typename Live>
+__device__ __forceinline__ void stage_reg_bit(double (&key)[KPL], Live live) {
+#pragma unroll
+    for (int r = 0; r < KPL; ++r)
+        if ((r & (1 << RB)) == 0 && live(r)) cmp_exchange(key[r], key[r | (1 << RB)]);
+}
+template <int KPL, int RB_HI, int RB_LO, typename Live>
+__device__ __forceinline__ void stages_reg_bits(double (&key)[KPL], Live live) {
+    if constexpr (RB_HI >= RB_LO) {
+        stage_reg_bit<KPL, RB_HI>(key, live);
+        stages_reg_bits<KPL, RB_HI - 1, RB_LO>(key, live);
+    }
+}
+
+// Batcher's odd-even merge sort of key[LO .. LO + N), ascending (all indices are compile-time constants).
+template <int KPL, int LO, int N, int R>
+__device__ __forceinline__ void oddeven_merge(double (&key)[KPL]) {
+    constexpr int kStep = R * 2;
+    if constexpr (kStep < N) {
+        oddeven_merge<KPL, LO, N, kStep>(key);
+        oddeven_merge<KPL, LO + R, N, kStep>(key);
+#pragma unroll
+        for (int i = LO + R; i + R < LO + N; i += kStep) cmp_exchange(key[i], key[i + R]);
+    } else {
+        cmp_exchange(key[LO], key[LO + R]);
+    }
+}
+template <int KPL, int LO, int N>
+__device__ __forceinline__ void oddeven_sort(double (&key)[KPL]) {
+    if constexpr (N > 1) {
+        oddeven_sort<KPL, LO, N / 2>(key);
+        oddeven_sort<KPL, LO + N / 2, N / 2>(key);
+        oddeven_merge<KPL, LO, N, 1>(key);
+    }
+}
+
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
+template <int KPL>
+__device__ __forceinline__ void flip_sign(double (&key)[KPL], uint32_t mask) {
+#pragma unroll
+    for (int r = 0; r < KPL; ++r)
+        key[r] = __hiloint2double((int)((uint32_t)__double2hiint(key[r]) ^ mask), __double2loint(key[r]));
+}
+
+// Value of x in the lane `lane ^ MASK` (MASK = 16 or 32).
+template <int MASK>
+__device__ __forceinline__ double partner(double x, int lane) {
+    const int lo = __builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, __double2loint(x));
+    const int hi = __builtin_amdgcn_ds_bpermute((lane ^ MASK) << 2, __double2hiint(x));
+    return __hiloint2double(hi, lo);
+}
+
+// Between the phases nothing is to be moved: with free rein the scheduler stretches live ranges across them
+// and the kernel no longer fits two wavefronts per SIMD without spilling.
+#define PODS_PHASE_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Two wavefronts per SIMD (the 64 keys alone take 128 registers); three fit only with spills and measured
+// slower, and 4096 wavefronts fill two rounds of two exactly.
+template <int KPL>
+__global__ __launch_bounds__(256, 2) void select_quarter_kernel(const float* __restrict__ rewards, int B,
+                                                             int32_t* __restrict__ sel_idx,
+                                                             int32_t* __restrict__ sel_k) {
+    constexpr int kR = ilog2(KPL);         // register bits
+    constexpr int kN = 4 * KPL, kM = KPL;  // n rollouts, m kept
+    constexpr int kPer = KPL / 4;          // sorted positions of each outer quarter, and candidates, per lane
+    static_assert(kR >= 2 && (1 << kR) == KPL, "KPL is a power of two, at least 4");
+    const int lane = threadIdx.x & (kWave - 1);
+    const int l0 = (lane >> 4) & 1, l1 = lane >> 5;     // the two lane bits of the group
+    const int64_t group = ((int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave) * 16 + (lane & 15);
+    const bool live = group < B;
+
+    // ---- load and key: the lane takes every fourth float4 of the row (the group's four lanes read 64
+    // contiguous bytes per instruction); the element's index rides in the key, so which lane sorts
+    // which elements is free.  Lanes whose run must come out descending start with negated keys.
+    const float4* row = reinterpret_cast<const float4*>(rewards + (size_t)(live ? group : 0) * kN);
+    const int quad = 2 * l1 + l0;
+    const uint32_t sign_a = ((l0 ^ l1) != 0) ? 0x80000000u : 0u;
+    double key[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL / 4; ++i) {
+        const float4 v = row[4 * i + quad];
+        const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t b = __float_as_uint(x[c] + 0.0f);   // -0.0 -> +0.0
+            const uint32_t ou = b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);   // unsigned order == float order
+            const uint32_t lo = (ou << kIdxBits) | (uint32_t)(quad << 2) | (uint32_t)(16 * i + c);
+            const uint32_t hi = (ou >> (32 - kIdxBits)) | 0x40000000u | sign_a;
+            key[4 * i + c] = __hiloint2double((int)hi, (int)lo);
+        }
+    }
+    auto all = [](int) { return true; };
+    PODS_PHASE_FENCE();
+
+    // ---- each lane: KPL keys ascending as stored
+    oddeven_sort<KPL, 0, KPL>(key);
+
+    // ---- merge of pairs of lanes (16 apart) into runs of 2 KPL.  Element bit kR sits in lane bit 0.
+    flip_sign<KPL>(key, l0 ? 0x80000000u : 0u);                  // odd lanes now descend
+    transpose_bit<KPL, 0, 0>(key, all);                          // lane bit 0 <- e0, register bit 0 <- e(kR)
+    stage_reg_bit<KPL, 0>(key, all);                             // stride KPL
+    stages_reg_bits<KPL, kR - 1, 1>(key, all);                   // strides KPL/2 .. 2
+    transpose_bit<KPL, 0, 1>(key, all);                          // lane bit 0 <- e1, register bit 1 <- e0
+    stage_reg_bit<KPL, 1>(key, all);                             // stride 1
+    // now: lane bit 1 = e(kR+1), lane bit 0 = e1, register bit 0 = e(kR), bit 1 = e0, bit j = ej (j >= 2)
+
+    // ---- merge of the two runs of 2 KPL (lanes 32 apart) into the sorted group, outer quarters only
+    flip_sign<KPL>(key, l1 ? 0x80000000u : 0u);                  // the upper run now descends (all keys true)
+    transpose_bit<KPL, 1, 1>(key, all);                          // lane bit 1 <- e0, register bit 1 <- e(kR+1)
+    stage_reg_bit<KPL, 1>(key, all);                             // stride 2 KPL
+    stage_reg_bit<KPL, 0>(key, all);                             // stride KPL
+    // registers with bits (1, 0) = 00 hold the lowest quarter, 11 the highest; 01 and 10 are never read again
+    auto outer = [](int r) { return (r & 3) == 0 || (r & 3) == 3; };
+    stages_reg_bits<KPL, kR - 1, 2>(key, outer);                 // strides KPL/2 .. 4
+    transpose_bit<KPL, 1, kR - 1>(key, outer);                   // lane bit 1 <- e(kR-1), register bit kR-1 <- e0
+    transpose_bit<KPL, 0, kR - 2>(key, outer);                   // lane bit 0 <- e(kR-2), register bit kR-2 <- e1
+    stage_reg_bit<KPL, kR - 2>(key, outer);                      // stride 2
+    stage_reg_bit<KPL, kR - 1>(key, outer);                      // stride 1
+    // Sorted position p: bit kR+1 = register bit 1, bit kR = register bit 0, bits kR-1, kR-2 = lane bits 1, 0,
+    // bits kR-3 .. 2 = the same register bits, bit 1 = register bit kR-2, bit 0 = register bit kR-1.
+    PODS_PHASE_FENCE();
+    auto reg_of = [](int i, bool high) {   // register holding offset i (0 .. kPer-1) of this lane's block
+        int r = high ? 3 : 0;
+        r |= (i & ~3) & ((1 << (kR - 2)) - 1);                   // offset bits kR-3 .. 2
+        r |= ((i >> 1) & 1) << (kR - 2);
+        r |= (i & 1) << (kR - 1);
+        return r;
+    };
+
+    // ---- Theorem 1 and Alg. 2 steps 2-6.  This lane owns offsets [a, a + kPer) of the m lowest and of the
+    // m highest sorted positions, i.e. the candidate splits k = m - (a + i), i = 0 .. kPer-1.
+    const int a = kPer * quad;
+    // rewards as float32 and the keys' low words (which end in the index): 3 registers per position instead
+    // of the 6 that double-precision rewards and separate indices would take
+    float lo_r[kPer], hi_r[kPer];
+    uint32_t lo_w[kPer], hi_w[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        lo_r[i] = key_reward(key[reg_of(i, false)]);
+        hi_r[i] = key_reward(key[reg_of(i, true)]);
+        lo_w[i] = (uint32_t)__double2loint(key[reg_of(i, false)]);
+        hi_w[i] = (uint32_t)__double2loint(key[reg_of(i, true)]);
+    }
+    PODS_PHASE_FENCE();
+    double bl1 = 0.0, bl2 = 0.0, bh1 = 0.0, bh2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const double x = (double)lo_r[i];
+        bl1 += x;
+        bl2 += x * x;
+    }
+#pragma unroll
+    for (int i = kPer - 1; i >= 0; --i) {
+        const double x = (double)hi_r[i];
+        bh1 += x;
+        bh2 += x * x;
+    }
+    // The candidate walk below converts the rewards to double again: without this the compiler keeps the 32
+    // doubles and their 32 squares of the block sums alive across the scans (128 registers).
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) asm volatile("" : "+v"(lo_r[i]), "+v"(hi_r[i]));
+    PODS_PHASE_FENCE();
+    // sums of the low range below this lane's block, of the high range above it
+    const double tl1 = partner<16>(bl1, lane), tl2 = partner<16>(bl2, lane);
+    const double th1 = partner<16>(bh1, lane), th2 = partner<16>(bh2, lane);
+    const double ul1 = partner<32>(bl1 + tl1, lane), ul2 = partner<32>(bl2 + tl2, lane);
+    const double uh1 = partner<32>(bh1 + th1, lane), uh2 = partner<32>(bh2 + th2, lane);
+    double p1 = (l1 ? ul1 : 0.0) + (l0 ? tl1 : 0.0);     // low positions before offset a
+    double p2 = (l1 ? ul2 : 0.0) + (l0 ? tl2 : 0.0);
+    double u1 = (l1 ? 0.0 : uh1) + (l0 ? 0.0 : th1);     // high positions from offset a + kPer on
+    double u2 = (l1 ? 0.0 : uh2) + (l0 ? 0.0 : th2);
+    p1 += bl1;                                           // low positions before offset a + kPer
+    p2 += bl2;
+    const double dm = (double)kM;
+    double best = -__builtin_huge_val();
+    int best_k = 0x7fffffff;
+    if (quad == 3) {   // k = 0, the m lowest: the last lane's block ends at position m
+        best = dm * p2 - p1 * p1;
+        best_k = 0;
+    }
+#pragma unroll
+    for (int i = kPer - 1; i >= 0; --i) {   // ascending k = m - (a + i)
+        const double xl = (double)lo_r[i], xh = (double)hi_r[i];
+        p1 -= xl;                            // low positions before offset a + i
+        p2 -= xl * xl;
+        u1 += xh;                            // high positions from offset a + i on
+        u2 += xh * xh;
+        if (hi_r[i] != lo_r[i]) {            // else same multiset as split k-1
+            const double S = p1 + u1;
+            const double Q = p2 + u2;
+            const double D = dm * Q - S * S;
+            if (D > best) { best = D; best_k = kM - (a + i); }
+        }
+    }
+    // best over the group's four lanes: the larger score, on equal scores the smaller k
+#pragma unroll
+    for (int step = 0; step < 2; ++step) {
+        const double ob = step == 0 ? partner<16>(best, lane) : partner<32>(best, lane);
+        const int ok = __builtin_amdgcn_ds_bpermute((lane ^ (step == 0 ? 16 : 32)) << 2, best_k);
+        if (ob > best || (ob == best && ok < best_k)) { best = ob; best_k = ok; }
+    }
+
+    PODS_PHASE_FENCE();
+    // ---- emit the (m-k) lowest then the k highest: output slot j = a + i
+    if (live) {
+        int32_t* out = sel_idx + (size_t)group * kM + a;
+#pragma unroll
+        for (int i = 0; i < kPer; i += 4) {
+            int4 w;
+            constexpr uint32_t kIdxMask = (1u << kIdxBits) - 1u;
+            w.x = (int)(((a + i + 0 < kM - best_k) ? lo_w[i + 0] : hi_w[i + 0]) & kIdxMask);
+            w.y = (int)(((a + i + 1 < kM - best_k) ? lo_w[i + 1] : hi_w[i + 1]) & kIdxMask);
+            w.z = (int)(((a + i + 2 < kM - best_k) ? lo_w[i + 2] : hi_w[i + 2]) & kIdxMask);
+            w.w = (int)(((a + i + 3 < kM - best_k) ? lo_w[i + 3] : hi_w[i + 3]) & kIdxMask);
+            *reinterpret_cast<int4*>(out + i) = w;
+        }
+        if (sel_k != nullptr && quad == 0) sel_k[group] = best_k;
+    }
+}
+
+template <int KPL>
+pods_status launch_quarter(const float* rewards, int32_t B, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
+    const unsigned grid = (unsigned)ceil_div(B, 4 * 16);   // 4 waves of 16 groups
+    PODS_LAUNCH("pods_select", stream, select_quarter_kernel<KPL>, dim3(grid), dim3(256), 0, stream, rewards, B, sel_idx,
+                sel_k);
+    return check_launch("pods_select");
+}
+
 template <int KPL, int G>
 pods_status launch_variant(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n, int32_t m,
                            int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
@@ -457,6 +737,12 @@ pods_status launch_select(const float* rewards, const uint32_t* rand_keys, int32
                           int32_t rule, int32_t* sel_idx, int32_t* sel_k, hipStream_t stream) {
 #define PODS_SELECT_VARIANT(KPL, G) \
     return launch_variant<KPL, G>(rewards, rand_keys, B, n, m, rule, sel_idx, sel_k, stream)
+    // max-variance, a quarter kept, 16-byte-aligned rows: the all-in-lane kernel
+    if (rule == PODS_RULE_MAXVAR && n == 4 * m && ((reinterpret_cast<uintptr_t>(rewards) | reinterpret_cast<uintptr_t>(sel_idx)) & 15) == 0) {
+        if (n == 256) return launch_quarter<64>(rewards, B, sel_idx, sel_k, stream);
+        if (n == 128) return launch_quarter<32>(rewards, B, sel_idx, sel_k, stream);
+        if (n == 64) return launch_quarter<16>(rewards, B, sel_idx, sel_k, stream);
+    }
     if (n <= 16) PODS_SELECT_VARIANT(4, 4);
     if (n <= 32) PODS_SELECT_VARIANT(8, 4);
     if (n <= 64) PODS_SELECT_VARIANT(16, 4);

@@ -52,7 +52,7 @@ def test_select_stress_config_full_size(pods):
 @pytest.mark.parametrize("n,m,B", [(1, 1, 3), (2, 1, 5), (7, 3, 9), (16, 16, 4), (63, 17, 11), (64, 64, 3),
                                    (65, 5, 7), (100, 33, 13), (129, 128, 5), (255, 64, 6), (300, 100, 9),
                                    (512, 128, 8), (1000, 333, 5), (2048, 64, 3), (4096, 1024, 2),
-                                   (4095, 4095, 2)])
+                                   (4095, 4095, 2), (64, 16, 37), (128, 32, 21), (256, 64, 19)])
 def test_select_ragged_shapes(pods, n, m, B):
     rng = np.random.default_rng(n * 131 + m)
     for kind in range(4):
