@@ -58,7 +58,9 @@ typedef enum {
     PODS_ERR_RUNTIME = 4       /* a HIP launch failed; pods_last_error() has the HIP message    */
 } pods_status;
 
-typedef enum { PODS_F32 = 0, PODS_BF16 = 1 } pods_dtype;
+/* The last member of each enum only widens it to 32 bits, so that any int a caller passes is a value the
+ * library may inspect and reject; it is not a value to pass. */
+typedef enum { PODS_F32 = 0, PODS_BF16 = 1, PODS_DTYPE_INT32_ = 0x7fffffff } pods_dtype;
 
 /* Max-variance down-sampling D_maxv (Sec. 3.3).  For each of B prompt groups, chooses the m of
  * n rewards whose (population) variance is maximal.  By Lemma 3.1 the optimum is the (m-k)
@@ -114,7 +116,8 @@ typedef enum {
     PODS_RULE_MAXVAR = 0,
     PODS_RULE_MAXR = 1,
     PODS_RULE_PERC = 2,
-    PODS_RULE_RAND = 3
+    PODS_RULE_RAND = 3,
+    PODS_RULE_INT32_ = 0x7fffffff
 } pods_rule;
 
 pods_status pods_downsample(const float* rewards, const uint32_t* rand_keys, int32_t B, int32_t n,

@@ -1,7 +1,7 @@
 """Pins for the selector oracle (Alg. 2, Lemma 3.1, Theorems 1 and 2).  CPU only."""
 import itertools
 from fractions import Fraction
-
+import os
 import numpy as np
 import pytest
 
@@ -160,3 +160,29 @@ def test_theorem2_cases_from_the_golden_file():
             assert len(set(sel)) == m and int(sum(r[i] for i in sel)) == want, (n, m, c1)
         idx, _, _ = fast.select(r[None], m)
         assert int(r[idx[0]].sum()) == want, (n, m, c1)
+
+
+def _exact_rows(args):
+    rows, m = args
+    return [po.select_exact(r, m) for r in rows]
+
+
+def test_c_oracle_equals_exact_rule_on_a_slice_of_the_stress_config():
+    """The batched C oracle is the reference the GPU selector is compared with on all 65536 groups of the
+    selector-stress config; here it is itself held to the paper's rule in exact rational arithmetic on the
+    config's first 2048 groups (n = 256, m = 64; continuous rewards, about a tenth of the groups constant)."""
+    import multiprocessing as mp
+    from paper_2504_13818_amd import inputs
+    r = inputs.rewards(3, B=2048)
+    idx, k, _ = fast.select(r, 64)
+    workers = min(8, os.cpu_count() or 1)
+    chunks = [(r[i::workers], 64) for i in range(workers)]
+    with mp.get_context("fork").Pool(workers) as pool:
+        parts = pool.map(_exact_rows, chunks)
+    flat = 0
+    for w, part in enumerate(parts):
+        for j, (eidx, ek) in enumerate(part):
+            b = w + j * workers
+            assert list(idx[b]) == eidx and k[b] == ek, f"group {b}"
+            flat += int(r[b].max() == r[b].min())
+    assert flat > 100                               # the slice holds constant groups too
