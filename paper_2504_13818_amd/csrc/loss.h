@@ -102,8 +102,8 @@ struct LossPlan {
                       // power of two apart
     int64_t vld;      // V rounded up to kTile: rows of the fp16 weight copy, columns of the transposed one
     int loss_blocks;
-    size_t off_hdr, off_gmax, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_pmax, off_psum,
-        off_losspart, off_wtt, off_htt, off_wt, off_ht, off_dz, total;
+    size_t off_hdr, off_gmax, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_cscale, off_pmax,
+        off_psum, off_qscale, off_losspart, off_wtt, off_htt, off_wt, off_ht, off_dz, total;
 };
 
 // mode 0: recommended size; mode 1: minimum size; otherwise `mode` is the number of bytes

@@ -26,8 +26,11 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     p.off_zy = take(sizeof(float) * (size_t)p.ncap_ld);
     p.off_g = take(sizeof(float) * (size_t)p.ncap_ld);
     p.off_coef = take(sizeof(float) * (size_t)p.ncap_ld);
+    p.off_cscale = take(sizeof(float) * (size_t)p.ncap_ld);
     p.off_pmax = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
     p.off_psum = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
+    // matrix-core path: fp16 power-of-two factor per (vocabulary tile, token) of the softmax numerators
+    p.off_qscale = take(p.mfma ? sizeof(uint16_t) * (size_t)p.ncap_ld * p.slots : 0);
     p.off_losspart = take(sizeof(double) * (size_t)p.loss_blocks);
     // per-block maxima of |g|: one entry per kTile rows covers every possible block size
     p.off_gmax = take(sizeof(uint32_t) * (size_t)(p.ncap_ld / kTile));
@@ -169,14 +172,22 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
     }
 }
 
-// Per valid token of the rows [row0, row_end): the forward pass's partial (max, sum exp) pairs, one per
-// vocabulary tile, merged into log-sum-exp.  64 tokens per workgroup; the four waves take every fourth
-// partial each (coalesced across tokens, many loads in flight) and are merged through LDS.
+// Per valid token of the rows [row0, row_end): the forward pass's partials, one per vocabulary tile, merged
+// into log-sum-exp.  64 tokens per workgroup; the four waves take every fourth partial each (coalesced across
+// tokens, many loads in flight) and are merged through LDS.
+// BASE2 = false (plain path): a partial is (m, sum exp(z - m)).
+// BASE2 = true (matrix-core path): a partial is (E, sum exp(z) 2^-E) with E an integer, so partials combine
+// by exact powers of two; besides lse the kernel writes, for the softmax numerators 2^14 exp(z) 2^-E kept by
+// the forward pass: cscale[p] = 2^Eref exp(-lse) in [1, 2) with Eref = ceil(lse log2 e), and
+// qscale[tile][p] = 2^(E - Eref) <= 1 in fp16 (exact; 0 below 2^-24), so that
+// 2^14 softmax = numerator * qscale * cscale.
+template <bool BASE2>
 __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__ hdr,
                                                   const float* __restrict__ pmax,
                                                   const float* __restrict__ psum, int slots,
                                                   int64_t slot_stride, int64_t row0, int64_t row_end,
-                                                  float* __restrict__ lse_out) {
+                                                  float* __restrict__ lse_out, float* __restrict__ cscale,
+                                                  _Float16* __restrict__ qscale) {
     __shared__ float sm[4][64], sl[4][64];
     const int64_t n_valid = hdr->n_valid < row_end ? hdr->n_valid : row_end;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -189,7 +200,8 @@ __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__
             const float l = psum[s * slot_stride + p];
             if (m > -__builtin_huge_valf()) {
                 const float Mn = fmaxf(M, m);
-                L = L * __expf(M - Mn) + l * __expf(m - Mn);
+                if constexpr (BASE2) L = ldexpf(L, (int)fmaxf(M - Mn, -200.0f)) + ldexpf(l, (int)(m - Mn));
+                else L = L * __expf(M - Mn) + l * __expf(m - Mn);
                 M = Mn;
             }
         }
@@ -197,13 +209,37 @@ __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__
     sm[w][lane] = M;
     sl[w][lane] = L;
     __syncthreads();
-    if (w == 0 && p < n_valid) {
-        float Mt = fmaxf(fmaxf(sm[0][lane], sm[1][lane]), fmaxf(sm[2][lane], sm[3][lane]));
+    float eref = 0.0f;
+    if (p < n_valid) {   // every wave merges the four partial results the same way
+        const float Mt = fmaxf(fmaxf(sm[0][lane], sm[1][lane]), fmaxf(sm[2][lane], sm[3][lane]));
         float Lt = 0.0f;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (sm[i][lane] > -__builtin_huge_valf()) Lt += sl[i][lane] * expf(sm[i][lane] - Mt);
-        lse_out[p] = Mt + logf(Lt);
+            if (sm[i][lane] > -__builtin_huge_valf())
+                Lt += BASE2 ? ldexpf(sl[i][lane], (int)(sm[i][lane] - Mt)) : sl[i][lane] * expf(sm[i][lane] - Mt);
+        if constexpr (BASE2) {
+            const float lse2 = Mt + log2f(Lt);
+            eref = ceilf(lse2);
+            if (w == 0) {
+                lse_out[p] = lse2 * 0.6931471805599453f;
+                cscale[p] = exp2f(eref - lse2);
+            }
+        } else if (w == 0) {
+            lse_out[p] = Mt + logf(Lt);
+        }
+    }
+    if constexpr (BASE2) {
+        // rows past N up to the end of the last token tile are read by the gradient kernels (against zero
+        // operands): their factors are zeros, not whatever the workspace held
+        const int64_t tile_end = (hdr->n_valid + 255) / 256 * 256;
+        if (p < n_valid) {
+            for (int s = w; s < slots; s += 4) {
+                const float e = pmax[s * slot_stride + p];
+                qscale[s * slot_stride + p] = (_Float16)ldexpf(1.0f, (int)fmaxf(e - eref, -30.0f));
+            }
+        } else if (p >= hdr->n_valid && p < tile_end && p < row_end) {
+            for (int s = w; s < slots; s += 4) qscale[s * slot_stride + p] = (_Float16)0.0f;
+        }
     }
 }
 
@@ -213,19 +249,19 @@ __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__
 // KL estimator (Table 2 lists the coefficient).  Block partial sums of the loss in double.
 __global__ __launch_bounds__(256) void surrogate_kernel(
     LossHeader* __restrict__ hdr, const int32_t* __restrict__ row_map,
-    const float* __restrict__ lse_in, const float* __restrict__ zy, const float* __restrict__ old_logp, const float* __restrict__ ref_logp,
+    const float* __restrict__ lse_in, const float* __restrict__ cscale, const float* __restrict__ zy, const float* __restrict__ old_logp, const float* __restrict__ ref_logp,
     float kl_coef, const float* __restrict__ adv,
     const int32_t* __restrict__ lengths, int R, int T, float clip_eps, float grad_scale,
     float* __restrict__ g_out, float* __restrict__ coef_out,
     float* __restrict__ logp_out, double* __restrict__ loss_part, int64_t row0, int64_t row_end,
     uint32_t* __restrict__ gmax_block) {
     __shared__ double red[4];
-    __shared__ float redg[4];
+    __shared__ float redg[4], redq[4];
     __shared__ int redc[4];
     const int64_t n_valid = hdr->n_valid < row_end ? hdr->n_valid : row_end;
     const int64_t p = row0 + (int64_t)blockIdx.x * 256 + threadIdx.x;
     double contrib = 0.0;
-    float gabs = 0.0f;
+    float gabs = 0.0f, gqabs = 0.0f;
     bool cut = false;
     if (p < n_valid) {
         const float lse = lse_in[p];
@@ -249,9 +285,12 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
             dobj += kl_coef * em1;
         }
         const float gp = -c * dobj * grad_scale;
-        g_out[p] = gp;
+        // the matrix-core path's softmax operand lacks a per-token factor in [1, 2): it rides on the weight
+        const float gq = cscale != nullptr ? gp * cscale[p] : gp;
+        g_out[p] = gq;
         coef_out[p] = gp * -expm1f(logp);  // d loss / d z_y = g (1 - softmax_y)
         gabs = fabsf(gp);
+        gqabs = fabsf(gq);
         if (logp_out != nullptr) logp_out[flat] = logp;
         contrib = -(double)c * (double)obj;
     }
@@ -259,11 +298,13 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
     for (int off = 32; off >= 1; off >>= 1) {
         contrib += __shfl_xor(contrib, off, 64);
         gabs = fmaxf(gabs, __shfl_xor(gabs, off, 64));
+        gqabs = fmaxf(gqabs, __shfl_xor(gqabs, off, 64));
     }
     const int ncut = __popcll(__ballot(cut));
     if ((threadIdx.x & 63) == 0) {
         red[threadIdx.x >> 6] = contrib;
         redg[threadIdx.x >> 6] = gabs;
+        redq[threadIdx.x >> 6] = gqabs;
         redc[threadIdx.x >> 6] = ncut;
     }
     __syncthreads();
@@ -272,10 +313,9 @@ __global__ __launch_bounds__(256) void surrogate_kernel(
         const int nc = redc[0] + redc[1] + redc[2] + redc[3];
         if (nc > 0) atomicAdd(&hdr->clipped, nc);   // an integer count: order-independent
         const float gm = fmaxf(fmaxf(redg[0], redg[1]), fmaxf(redg[2], redg[3]));
-        if (gm > 0.0f) {   // maxima: order-independent
-            atomicMax(gmax_block, __float_as_uint(gm));
-            atomicMax(&hdr->gmax_bits, __float_as_uint(gm));
-        }
+        const float gq = fmaxf(fmaxf(redq[0], redq[1]), fmaxf(redq[2], redq[3]));
+        if (gm > 0.0f) atomicMax(&hdr->gmax_bits, __float_as_uint(gm));   // maxima: order-independent
+        if (gq > 0.0f) atomicMax(gmax_block, __float_as_uint(gq));
     }
 }
 
@@ -297,15 +337,22 @@ __global__ __launch_bounds__(1024) void finalize_loss_kernel(const double* __res
 
 pods_status launch_surrogate(const LossArgs& a, const LossPlan& p, int64_t row0, int64_t nrows, int block) {
     unsigned char* ws = a.workspace;
-    PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel, dim3((unsigned)ceil_div(nrows, 64)), dim3(256), 0, a.stream,
-                reinterpret_cast<const LossHeader*>(ws + p.off_hdr), reinterpret_cast<const float*>(ws + p.off_pmax),
-                reinterpret_cast<const float*>(ws + p.off_psum), p.slots, p.ncap_ld, row0, row0 + nrows,
-                reinterpret_cast<float*>(ws + p.off_lse));
+    float* cscale = p.mfma ? reinterpret_cast<float*>(ws + p.off_cscale) : nullptr;
+    if (p.mfma)
+        PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel<true>, dim3((unsigned)ceil_div(nrows, 64)), dim3(256), 0, a.stream,
+                    reinterpret_cast<const LossHeader*>(ws + p.off_hdr), reinterpret_cast<const float*>(ws + p.off_pmax),
+                    reinterpret_cast<const float*>(ws + p.off_psum), p.slots, p.ncap_ld, row0, row0 + nrows,
+                    reinterpret_cast<float*>(ws + p.off_lse), cscale, reinterpret_cast<_Float16*>(ws + p.off_qscale));
+    else
+        PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel<false>, dim3((unsigned)ceil_div(nrows, 64)), dim3(256), 0, a.stream,
+                    reinterpret_cast<const LossHeader*>(ws + p.off_hdr), reinterpret_cast<const float*>(ws + p.off_pmax),
+                    reinterpret_cast<const float*>(ws + p.off_psum), p.slots, p.ncap_ld, row0, row0 + nrows,
+                    reinterpret_cast<float*>(ws + p.off_lse), nullptr, nullptr);
     pods_status st = check_launch("log-sum-exp");
     if (st != PODS_OK) return st;
     PODS_LAUNCH("surrogate", a.stream, surrogate_kernel, dim3((unsigned)ceil_div(nrows, 256)), dim3(256), 0, a.stream,
                 reinterpret_cast<LossHeader*>(ws + p.off_hdr), reinterpret_cast<const int32_t*>(ws + p.off_rowmap),
-                reinterpret_cast<const float*>(ws + p.off_lse), reinterpret_cast<const float*>(ws + p.off_zy), a.old_logp, a.ref_logp, a.kl_coef,
+                reinterpret_cast<const float*>(ws + p.off_lse), cscale, reinterpret_cast<const float*>(ws + p.off_zy), a.old_logp, a.ref_logp, a.kl_coef,
                 a.adv, a.lengths, a.R, a.T, a.clip_eps, a.grad_scale,
                 reinterpret_cast<float*>(ws + p.off_g), reinterpret_cast<float*>(ws + p.off_coef), a.logp_out,
                 reinterpret_cast<double*>(ws + p.off_losspart), row0, row0 + nrows,
