@@ -6,16 +6,18 @@
 // v_mfma_f32_32x32x16_f16 on fp16 working copies (exact while the scaled value stays in fp16's normal
 // range):
 //
-//   forward    z[v][t]  = sum_k Wt[k][v]  Ht[k][t]      -> per token and vocabulary tile: m = max z, sum exp(z - m),
-//                                                          z_y, and the numerators 2^14 exp(z - m) as fp16
-//   rescale    q[t][v]  = numerator * exp(m - lse_t)    -> q = 2^14 softmax (0 at v = y), in place
+//   forward    z[v][t]  = sum_k Wt[k][v]  Ht[k][t]      -> per token and vocabulary tile: an integer E with
+//                                                          2^E >= exp(max z), sum exp(z) 2^-E, z_y, and the
+//                                                          numerators 2^14 exp(z) 2^-E as fp16
+//   normalise  q[t][v]  = numerator * 2^(E - Eref_t)    -> q = 2^14 softmax / c_t (0 at v = y), in place, exact
 //   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times -g_t, over the whole vocabulary
 //   d_w_lm     dW[k][v] = sum_t H16[t][k] q[t][v]       -> accumulated over the token blocks
 //
 // The softmax numerators of ONE token block, q[nb][V], are the only [tokens, vocabulary]-shaped array that
 // ever exists (10 GB of the 90 GB the full logits would take at the Qwen2.5-3B-shaped sizes): keeping them
-// from the forward pass, under a per-tile offset that a cheap elementwise pass corrects once the
-// log-sum-exp is known, spares the backward pass a second logits contraction (2 N d V of the 8 N d V
+// from the forward pass, under a per-tile power-of-two offset that a cheap elementwise pass takes out once
+// the log-sum-exp is known (the remaining per-token factor c_t in [1, 2) rides on the token's weight g_t),
+// spares the backward pass a second logits contraction (2 N d V of the 8 N d V
 // floating-point operations a recomputing backward pass executes).
 //
 // An operand whose contraction index is its row index in memory (all of them except q in
@@ -60,13 +62,12 @@ constexpr int kOperandBytes = kTile * kBK * 2;     // 16 KiB: 256 rows x 64 B
 constexpr int kStageBytes = 2 * kOperandBytes;     // A then B
 constexpr int kStages = 4;                         // ring of LDS stages
 constexpr int kDist = kStages - 1;                 // k-tiles in flight ahead of the one being multiplied
-constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB (the gradient kernels add kStages small slots of factors)
+constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
 constexpr int kQPitch = 2 * kTile + 8;             // bytes per token row of the q tile staged in LDS
 constexpr int kStatsOffset = kTile * kQPitch > kLdsBytes ? kTile * kQPitch : kLdsBytes;   // past the staged q tile
 constexpr int kFwdLdsBytes = kStatsOffset + 2 * 2 * kTile * 4;   // + [2][256] maxima and [2][256] sums: 134 KiB
 constexpr int kHPitch = 4 * kTile + 16;            // bytes per token row of the d_hidden half-tile staged in LDS
-constexpr int kGradLdsBytes = kLdsBytes + kStages * 512;   // the ring and the factor slots of its stages
-constexpr int kDhLdsBytes = 128 * kHPitch > kGradLdsBytes ? 128 * kHPitch : kGradLdsBytes;   // 130 KiB
+constexpr int kDhLdsBytes = 128 * kHPitch > kLdsBytes ? 128 * kHPitch : kLdsBytes;   // 130 KiB
 constexpr float kLog2e = 1.4426950408889634f;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -221,76 +222,11 @@ __device__ __forceinline__ E read_frag(const unsigned char* stage, int rd, int k
 // reads, fetched 3 tiles too many per output tile: 5 % of the traffic and of the time when K is only
 // 64 tiles, as in the logits.)
 // On return nothing is in flight and the LDS ring may be reused after a barrier.
-// Scaling of the B operand's fragments on their way from LDS to the matrix pipe (the gradient kernels'
-// q operand holds softmax numerators under a per-(token, vocabulary tile) power-of-two offset):
-//   kScaleNone  nothing;
-//   kScaleRows  d_hidden: B rows are tokens; a lane's fragment of block ni belongs to one token, whose factor
-//               changes every 8 k-tiles (256 vocabulary entries);
-//   kScaleK     d_w_lm: the contraction runs over tokens; a lane's fragment holds 8 consecutive tokens of the
-//               k-tile, each with its own factor for this output tile's vocabulary tile.
-// The factors (fp16 powers of two, so the products are exact) come through LDS with the operand tiles: wave 0
-// requests the k-tile's factors just before the tile's own loads, into the slot of the tile's stage.
-enum { kScaleNone = 0, kScaleRows = 1, kScaleK = 2 };
-constexpr int kScaleSlotBytes = 512;               // 256 token factors (rows) or 32 (k); fp16
-struct ScaleSrc {
-    const unsigned char* base;   // first factor of this workgroup's rows (kScaleRows) or of its first k-tile (kScaleK)
-    int64_t step;                // bytes from one vocabulary tile (rows) or one k-tile (k) to the next
-    int tile;                    // k-tiles requested so far
-};
-
-template <int SC>
-__device__ __forceinline__ void request_scales(ScaleSrc& sc, unsigned slot_addr, const LaneGeom& g) {
-    if constexpr (SC != kScaleNone) {
-        const unsigned char* src = sc.base + (SC == kScaleRows ? (int64_t)(sc.tile >> 3) : (int64_t)sc.tile) * sc.step;
-        if (g.wave == 0 && g.lane < (SC == kScaleRows ? 32 : 4)) load_to_lds_16_asm(src + g.lane * 16, slot_addr);
-        ++sc.tile;
-    }
-}
-// The factors of the lane's fragments, read from a stage's slot.
-template <int SC>
-__device__ __forceinline__ void read_scales(const unsigned char* slot, const LaneGeom& g, int ks, f16x8 (&sv)[4]) {
-    if constexpr (SC == kScaleRows) {
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const _Float16 h = *reinterpret_cast<const _Float16*>(slot + (g.wn * 128 + ni * 32 + (g.lane & 31)) * 2);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) sv[ni][j] = h;
-        }
-    } else if constexpr (SC == kScaleK) {
-        sv[0] = *reinterpret_cast<const f16x8*>(slot + (ks * 16 + 8 * (g.lane >> 5)) * 2);
-    }
-}
-// In place, as inline assembly: written as plain arithmetic the compiler sinks these multiplications to the
-// fragments' first use (the start of the next phase, where the matrix pipe then waits for all of them) and
-// copies the fragments on the way.
-template <int SC, typename E>
-__device__ __forceinline__ void scale_frag(E& f, const f16x8 (&sv)[4], int ni) {
-    if constexpr (SC != kScaleNone) {
-        u32x4 x = __builtin_bit_cast(u32x4, f);
-        const u32x4 y = __builtin_bit_cast(u32x4, sv[SC == kScaleRows ? ni : 0]);
-        if constexpr (SC == kScaleRows) {   // one factor per fragment: the same register for all four products
-            asm volatile("v_pk_mul_f16 %0, %0, %4\n\tv_pk_mul_f16 %1, %1, %4\n\tv_pk_mul_f16 %2, %2, %4\n\t"
-                         "v_pk_mul_f16 %3, %3, %4"
-                         : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : "v"(y[0]));
-        } else {
-            asm volatile("v_pk_mul_f16 %0, %0, %4\n\tv_pk_mul_f16 %1, %1, %5\n\tv_pk_mul_f16 %2, %2, %6\n\t"
-                         "v_pk_mul_f16 %3, %3, %7"
-                         : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]) : "v"(y[0]), "v"(y[1]), "v"(y[2]), "v"(y[3]));
-        }
-        f = __builtin_bit_cast(E, x);
-    }
-}
-
-template <typename E, bool AKM, bool BKM, bool LOAD, int SC>
+template <typename E, bool AKM, bool BKM, bool LOAD>
 __device__ __forceinline__ void k_step(Operand& A, Operand& B, const unsigned char* cur, const unsigned char* nxt,
                                        unsigned char* dst, unsigned dsta, const LaneGeom& g, E (&fa)[2][4],
-                                       E (&fb)[2][4], f32x16 (&acc)[4][4], ScaleSrc& sc,
-                                       const unsigned char* cur_slot, const unsigned char* nxt_slot,
-                                       unsigned dst_slot, bool new_rows_next, f16x8 (&sv)[4]) {
+                                       E (&fb)[2][4], f32x16 (&acc)[4][4]) {
     constexpr bool kAsm = AKM || BKM;
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (LOAD) request_scales<SC>(sc, dst_slot, g);
-    if constexpr (SC == kScaleK) read_scales<SC>(cur_slot, g, 1, sv);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -317,7 +253,6 @@ __device__ __forceinline__ void k_step(Operand& A, Operand& B, const unsigned ch
                       fa[1][1] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 1, 1); }
         if (i == 3) { fa[1][2] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 2, 1);
                       fa[1][3] = read_frag<E, AKM>(cur, g.a_rd, g.a_km, g.e6, g.cx16, 3, 1); }
-        if (i >= 4) scale_frag<SC>(fb[1][i - 4], sv, i - 4);   // delivered by now; used from the barrier on
         __builtin_amdgcn_sched_barrier(0);
     }
     // loads return in order: with loads still being issued, everything but the newest kDist-1 tiles is
@@ -326,12 +261,6 @@ __device__ __forceinline__ void k_step(Operand& A, Operand& B, const unsigned ch
     else wait_vmcnt<0>();
     wait_lgkmcnt0();                 // this wave's reads of `cur` are done before others may refill it
     __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    // the next k-tile's factors (its stage has landed: the wait above covers it)
-    if constexpr (SC == kScaleK) read_scales<SC>(nxt_slot, g, 0, sv);
-    if constexpr (SC == kScaleRows) {
-        if (new_rows_next) read_scales<SC>(nxt_slot, g, 0, sv);
-    }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -345,24 +274,18 @@ __device__ __forceinline__ void k_step(Operand& A, Operand& B, const unsigned ch
                       fa[0][1] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 1, 0); }
         if (i == 3) { fa[0][2] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 2, 0);
                       fa[0][3] = read_frag<E, AKM>(nxt, g.a_rd, g.a_km, g.e6, g.cx16, 3, 0); }
-        if (i >= 4) scale_frag<SC>(fb[0][i - 4], sv, i - 4);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-template <typename E, bool AKM = false, bool BKM = false, int SC = kScaleNone>
+template <typename E, bool AKM = false, bool BKM = false>
 __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned char* lds,
-                                       const LaneGeom& g, f32x16 (&acc)[4][4], ScaleSrc sc = ScaleSrc{nullptr, 0, 0}) {
+                                       const LaneGeom& g, f32x16 (&acc)[4][4]) {
     constexpr bool kAsm = AKM || BKM;
     unsigned char* wave_base = lds + g.wave * 1024;
     const unsigned wave_lds = __builtin_amdgcn_readfirstlane(
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)wave_base);
-    // factor slots, one per stage, past the ring
-    const unsigned char* slots = lds + kLdsBytes;
-    const unsigned slots_lds = __builtin_amdgcn_readfirstlane(
-        (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(lds + kLdsBytes));
     E fa[2][4], fb[2][4];
-    f16x8 sv[4];
     __builtin_amdgcn_s_barrier();   // every wave has left the ring (previous use)
     const int ahead = KT < kDist ? KT : kDist;   // tiles requested before the first one is multiplied
 #pragma unroll
@@ -370,7 +293,6 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
         if (t < ahead) {
             unsigned char* dst = wave_base + t * kStageBytes;
             const unsigned dsta = wave_lds + t * kStageBytes;
-            request_scales<SC>(sc, slots_lds + t * kScaleSlotBytes, g);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
@@ -386,30 +308,23 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
     if (KT >= kDist) wait_vmcnt<8 * (kDist - 1)>();   // the first tile is in
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if constexpr (SC != kScaleNone) read_scales<SC>(slots, g, 0, sv);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         fa[0][i] = read_frag<E, AKM>(lds, g.a_rd, g.a_km, g.e6, g.cx16, i, 0);
         fb[0][i] = read_frag<E, BKM>(lds, g.b_rd, g.b_km, g.e6, g.cx16, i, 0);
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) scale_frag<SC>(fb[0][i], sv, i);
     int st = 0, fill = kDist;
     int kt = 0;
     for (; kt + kDist < KT; ++kt) {   // tile kt + kDist goes into the stage consumed in the previous iteration
         const int stn = (st + 1 == kStages) ? 0 : st + 1;
-        k_step<E, AKM, BKM, true, SC>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes,
-                                      wave_base + fill * kStageBytes, wave_lds + fill * kStageBytes, g, fa, fb, acc, sc,
-                                      slots + st * kScaleSlotBytes, slots + stn * kScaleSlotBytes,
-                                      slots_lds + fill * kScaleSlotBytes, ((kt + 1) & 7) == 0, sv);
+        k_step<E, AKM, BKM, true>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes,
+                                  wave_base + fill * kStageBytes, wave_lds + fill * kStageBytes, g, fa, fb, acc);
         st = stn;
         fill = (fill + 1 == kStages) ? 0 : fill + 1;
     }
     for (; kt < KT; ++kt) {           // the last tiles: nothing left to request
         const int stn = (st + 1 == kStages) ? 0 : st + 1;
-        k_step<E, AKM, BKM, false, SC>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes, nullptr, 0u, g, fa, fb, acc,
-                                       sc, slots + st * kScaleSlotBytes, slots + stn * kScaleSlotBytes, 0u,
-                                       ((kt + 1) & 7) == 0, sv);
+        k_step<E, AKM, BKM, false>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes, nullptr, 0u, g, fa, fb, acc);
         st = stn;
     }
     wait_lgkmcnt0();
@@ -438,8 +353,8 @@ __device__ __forceinline__ int acc_slot_of(int rel) {
 // tile, merged later by the log-sum-exp kernel), z_y, and the tile's softmax numerators 2^14 exp(z) 2^-E
 // rounded to fp16 (0 at v = y and past V), token-major, into the block's q array.  E is common to the tile's
 // two vocabulary waves (exchanged through LDS).  Once the token's log-sum-exp is known, the numerators are
-// 2^14 softmax up to one power of two per (token, vocabulary tile) and one factor in [1, 2) per token: the
-// gradient kernels apply the first to their fragments (exact in fp16), the second with the token's weight.
+// 2^14 softmax up to one power of two per (token, vocabulary tile), which the normalising pass applies (exact
+// in fp16), and one factor in [1, 2) per token, which the gradient kernels get with the token's weight.
 // One tile per workgroup (rather than a workgroup walking many vocabulary tiles) keeps the 32
 // workgroups of an XCD in step, which is what lets them share operand tiles in the 4 MiB L2.
 // A launch covers the token tiles of one token block (first row row0) and vocabulary tiles
@@ -597,6 +512,29 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 }
 
 // ------------------------------------------------------------------------------------------
+// Normalise (per token block, once its log-sum-exp is known): the forward pass's numerators times the power
+// of two of their (token, vocabulary tile), in place: exact in fp16 (results below 2^-24 vanish).  Afterwards
+// q = 2^14 softmax / c_t with the per-token factor c_t in [1, 2) that rides on the token's weight.
+// 16 bytes per lane; bound by HBM (2 x 2 bytes per logit of the block).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rescale_kernel(const LossHeader* __restrict__ hdr,
+                                                      const _Float16* __restrict__ qscale, int64_t slot_stride,
+                                                      int64_t row0, int granules, int64_t ldq,
+                                                      _Float16* __restrict__ q) {
+    const int64_t r = blockIdx.y;
+    const int64_t p = row0 + r;
+    if (p >= hdr->n_bwd) return;
+    const int gcol = blockIdx.x * 256 + threadIdx.x;
+    if (gcol >= granules) return;
+    const _Float16 s = qscale[(int64_t)(gcol >> 5) * slot_stride + p];   // 32 granules of 8 per vocabulary tile
+    _Float16* at = q + r * ldq + (int64_t)gcol * 8;
+    f16x8 x = *reinterpret_cast<const f16x8*>(at);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = x[j] * s;
+    *reinterpret_cast<f16x8*>(at) = x;
+}
+
+// ------------------------------------------------------------------------------------------
 // Backward: d_hidden[t][k] -= (g_t / (kQScale s_w)) sum_v q[t][v] W16[v][k], W16 = s_w W, over the whole
 // vocabulary, for the token tiles of one token block (the rows were initialised with the y-logit term)
 // ------------------------------------------------------------------------------------------
@@ -604,9 +542,8 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
                                                     const int32_t* __restrict__ row_map,
                                                     const float* __restrict__ gvec,
                                                     const uint16_t* __restrict__ w16,
-                                                    const uint16_t* __restrict__ q, int64_t ldq,
-                                                    const _Float16* __restrict__ qscale, int64_t slot_stride,
-                                                    int d, int V, int64_t row0, int ntt_grid,
+                                                    const uint16_t* __restrict__ q, int64_t ldq, int d,
+                                                    int V, int64_t row0, int ntt_grid,
                                                     float* __restrict__ d_hidden) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int64_t n_valid = hdr->n_bwd;
@@ -623,9 +560,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     f32x16 acc[4][4];
     zero_acc(acc);
     const int vwidth = (V + kTile - 1) / kTile * kTile;   // whole tiles that hold vocabulary
-    // factors of this token tile: qscale[vocabulary tile][token], 256 consecutive tokens per vocabulary tile
-    const ScaleSrc sc{reinterpret_cast<const unsigned char*>(qscale + tt * kTile), slot_stride * 2, 0};
-    k_loop<f16x8, true, false, kScaleRows>(A, B, vwidth / kBK, lds, g, acc, sc);
+    k_loop<f16x8, true, false>(A, B, vwidth / kBK, lds, g, acc);
 
     // The tile is added to d_hidden through LDS, half of its tokens at a time: a lane holds 4 consecutive
     // k of one token, so updating from registers would touch 32-byte pieces of 32 different rows per
@@ -702,7 +637,6 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
                                                     const uint32_t* __restrict__ gmax_block,
                                                     const uint16_t* __restrict__ h16,
                                                     const uint16_t* __restrict__ q, int64_t ldq,
-                                                    const _Float16* __restrict__ qscale, int64_t slot_stride,
                                                     int d, int V, int64_t row0, int64_t nb, int first_block,
                                                     int accumulate, float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -721,9 +655,7 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
     f32x16 acc[4][4];
     zero_acc(acc);
     const int KT = (int)((n_rows + kBK - 1) / kBK);
-    // factors of this vocabulary tile: qscale[vt][token], 32 consecutive tokens per k-tile
-    const ScaleSrc sc{reinterpret_cast<const unsigned char*>(qscale + vt * slot_stride + row0), kBK * 2, 0};
-    if (KT > 0) k_loop<f16x8, true, true, kScaleK>(A, B, KT, lds, g, acc, sc);
+    if (KT > 0) k_loop<f16x8, true, true>(A, B, KT, lds, g, acc);
     const float scale = -1.0f / (kQScale * g_range_scale(*gmax_block, hdr));
 
 #pragma unroll
@@ -950,7 +882,7 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
     pods_status st;
     if ((st = reserve(reinterpret_cast<const void*>(fwd_kernel), "token loss forward", kFwdLdsBytes)) != PODS_OK) return st;
     if ((st = reserve(reinterpret_cast<const void*>(dh_kernel), "token loss d_hidden", kDhLdsBytes)) != PODS_OK) return st;
-    if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm", kGradLdsBytes)) != PODS_OK) return st;
+    if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
 
     // once per call: transposed bf16 copies for the logits (they also find max |W|, max |h|), fp16 copy of W
     const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
@@ -968,6 +900,7 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
     const int64_t nvt = p.vld / kTile;
     const int64_t dt256 = ceil_div(a.d, kTile);
     const int64_t step_vt = kDefaultVocabChunk / kTile;
+    const int granules = (int)(p.vld / 8);
     for (int b = 0; b < p.nblocks; ++b) {
         const int64_t row0 = (int64_t)b * p.nb;
         const int64_t rows = p.ncap_ld - row0 < p.nb ? p.ncap_ld - row0 : p.nb;   // capacity of this block
@@ -983,6 +916,9 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
             if ((st = check_launch("token loss forward")) != PODS_OK) return st;
         }
         if ((st = launch_surrogate(a, p, row0, rows, b)) != PODS_OK) return st;
+        PODS_LAUNCH("token loss normalise", a.stream, rescale_kernel, dim3((unsigned)ceil_div(granules, 256), (unsigned)rows),
+                    dim3(256), 0, a.stream, hdr, qscale, p.ncap_ld, row0, granules, p.ldq, q);
+        if ((st = check_launch("token loss normalise")) != PODS_OK) return st;
         PODS_LAUNCH("convert H", a.stream, convert_kernel, dim3((unsigned)ceil_div(rows * per_row, 256)), dim3(256), 0,
                     a.stream, hdr, gmax + b, row_map, g, hidden, row0, rows, (int64_t)0, a.d, 1, h16);
         if ((st = check_launch("convert H")) != PODS_OK) return st;
@@ -991,11 +927,11 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
         if ((st = check_launch("token loss d_hidden (y logit)")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256),
                     kDhLdsBytes, a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
-                    reinterpret_cast<const uint16_t*>(q), p.ldq, qscale, p.ncap_ld, a.d, a.V, row0, (int)ntt, a.d_hidden);
+                    reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, (int)ntt, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(nvt, dt256)), dim3(256),
-                    kGradLdsBytes, a.stream, hdr, gmax + b, reinterpret_cast<const uint16_t*>(h16),
-                    reinterpret_cast<const uint16_t*>(q), p.ldq, qscale, p.ncap_ld, a.d, a.V, row0, rows, b == 0 ? 1 : 0,
+                    kLdsBytes, a.stream, hdr, gmax + b, reinterpret_cast<const uint16_t*>(h16),
+                    reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, rows, b == 0 ? 1 : 0,
                     (a.accumulate_d_w || b > 0) ? 1 : 0, a.d_w_lm);
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
     }
