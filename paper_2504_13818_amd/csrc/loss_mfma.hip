@@ -77,19 +77,15 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // inline assembly so that the compiler does not pair it with the LDS reads it schedules (it would
 // drain the whole vector-memory queue before each of them); completion is tracked by hand with
 // s_waitcnt vmcnt.
+// The global address is a wave-uniform base (a scalar register pair, advanced once per k-tile by two scalar
+// additions) plus the lane's fixed 32-bit offset: no vector arithmetic per load.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void load_to_lds_16_asm(const unsigned char* gptr, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+__device__ __forceinline__ void load_to_lds_16(uint64_t base, unsigned offset, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(offset), "s"(base)
+                 : "memory", "m0");
 }
 #pragma clang diagnostic pop
-// kernels whose LDS reads are all plain ds_read_b128 may use the builtin (no spurious waits there)
-template <bool ASM>
-__device__ __forceinline__ void load_to_lds_16(const unsigned char* gptr, unsigned char* lds_generic,
-                                               unsigned lds_addr) {
-    if constexpr (ASM) load_to_lds_16_asm(gptr, lds_addr);
-    else __builtin_amdgcn_global_load_lds(gptr, (lds_ptr_t)lds_generic, 16, 0, 0);
-}
 
 // s_waitcnt vmcnt(N), leaving expcnt and lgkmcnt alone (gfx9 encoding).
 template <int N>
@@ -103,23 +99,32 @@ __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC
 // of wave w, instruction i fills row 64 i + 16 w + l/4, slot l%4, and therefore fetches the granule
 // (l%4) ^ ((row >> 2) & 3) of that row: the XOR swizzle that makes the later ds_read_b128 fragment
 // loads (16 consecutive rows, one granule column per pass) hit 16 distinct bank groups.
-struct Operand {  // this thread's 4 source pointers (bytes) into one operand k-tile, and the k-tile stride
-    const unsigned char* ptr[4];
-    int64_t step;
+struct Operand {  // one operand's k-tiles: wave-uniform base of the current k-tile, this thread's 4 byte offsets
+    uint64_t base;
+    unsigned off[4];
+    int64_t step;   // bytes from one k-tile to the next
 };
+
+__device__ __forceinline__ uint64_t uniform_address(const void* p) {
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
 
 // Operand stored with the contraction index contiguous ("row-major rows x k"): tile = 256 rows x
 // 64 B.  Rows at or beyond `rows` are clamped to the last row (their products are masked or
-// multiplied by zeros by the caller).
+// multiplied by zeros by the caller).  Offsets are relative to row `row0`: at most 256 rows of ld elements
+// (below 2^32 bytes for every supported shape).
 __device__ __forceinline__ void operand_rows(Operand& op, const uint16_t* base, int64_t ld,
                                              int64_t row0, int64_t rows, int64_t col0) {
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
     const int gc = (l & 3) ^ ((l >> 4) & 3);
+    op.base = uniform_address(base + row0 * ld + col0);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int64_t row = row0 + 64 * i + 16 * w + (l >> 2);
         if (row >= rows) row = rows - 1;
-        op.ptr[i] = reinterpret_cast<const unsigned char*>(base + row * ld + col0 + gc * 8);
+        op.off[i] = (unsigned)(((row - row0) * ld + gc * 8) * 2);
     }
     op.step = 64;
 }
@@ -134,20 +139,16 @@ __device__ __forceinline__ void operand_rows(Operand& op, const uint16_t* base, 
 __device__ __forceinline__ void operand_kmajor(Operand& op, const uint16_t* base, int64_t ld,
                                                int64_t k0, int64_t col0, int64_t cols) {
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    op.base = uniform_address(base + k0 * ld + col0);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = 8 * i + 2 * w + (l >> 5);
         const int gc = (l & 31) ^ ((row & 3) << 2);
         int64_t col = col0 + gc * 8;
         if (col > cols - 8) col = cols - 8;
-        op.ptr[i] = reinterpret_cast<const unsigned char*>(base + (k0 + row) * ld + col);
+        op.off[i] = (unsigned)((row * ld + (col - col0)) * 2);
     }
     op.step = 32 * ld * 2;
-}
-
-__device__ __forceinline__ void advance(Operand& op, int64_t bytes) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) op.ptr[i] += bytes;
 }
 
 struct LaneGeom {
@@ -224,22 +225,17 @@ __device__ __forceinline__ E read_frag(const unsigned char* stage, int rd, int k
 // On return nothing is in flight and the LDS ring may be reused after a barrier.
 template <typename E, bool AKM, bool BKM, bool LOAD>
 __device__ __forceinline__ void k_step(Operand& A, Operand& B, const unsigned char* cur, const unsigned char* nxt,
-                                       unsigned char* dst, unsigned dsta, const LaneGeom& g, E (&fa)[2][4],
+                                       unsigned dsta, const LaneGeom& g, E (&fa)[2][4],
                                        E (&fb)[2][4], f32x16 (&acc)[4][4]) {
-    constexpr bool kAsm = AKM || BKM;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         { const int mi = (2 * i) >> 2, ni = (2 * i) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
         if constexpr (LOAD) {
-            if (i < 4) {
-                load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
-                A.ptr[i] += A.step;
-            } else {
-                load_to_lds_16<kAsm>(B.ptr[i - 4], dst + kOperandBytes + (i - 4) * 4096,
-                                     dsta + kOperandBytes + (i - 4) * 4096);
-                B.ptr[i - 4] += B.step;
-            }
+            if (i < 4) load_to_lds_16(A.base, A.off[i], dsta + i * 4096);
+            else load_to_lds_16(B.base, B.off[i - 4], dsta + kOperandBytes + (i - 4) * 4096);
+            if (i == 3) A.base += A.step;
+            if (i == 7) B.base += B.step;
         }
         __builtin_amdgcn_sched_barrier(0);
         { const int mi = (2 * i + 1) >> 2, ni = (2 * i + 1) & 3; acc[mi][ni] = mfma(fa[0][mi], fb[0][ni], acc[mi][ni]); }
@@ -281,28 +277,21 @@ __device__ __forceinline__ void k_step(Operand& A, Operand& B, const unsigned ch
 template <typename E, bool AKM = false, bool BKM = false>
 __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned char* lds,
                                        const LaneGeom& g, f32x16 (&acc)[4][4]) {
-    constexpr bool kAsm = AKM || BKM;
-    unsigned char* wave_base = lds + g.wave * 1024;
     const unsigned wave_lds = __builtin_amdgcn_readfirstlane(
-        (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)wave_base);
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(lds + g.wave * 1024));
     E fa[2][4], fb[2][4];
     __builtin_amdgcn_s_barrier();   // every wave has left the ring (previous use)
     const int ahead = KT < kDist ? KT : kDist;   // tiles requested before the first one is multiplied
 #pragma unroll
     for (int t = 0; t < kDist; ++t) {
         if (t < ahead) {
-            unsigned char* dst = wave_base + t * kStageBytes;
             const unsigned dsta = wave_lds + t * kStageBytes;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                load_to_lds_16<kAsm>(A.ptr[i], dst + i * 4096, dsta + i * 4096);
-                A.ptr[i] += A.step;
-            }
+            for (int i = 0; i < 4; ++i) load_to_lds_16(A.base, A.off[i], dsta + i * 4096);
+            A.base += A.step;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                load_to_lds_16<kAsm>(B.ptr[i], dst + kOperandBytes + i * 4096, dsta + kOperandBytes + i * 4096);
-                B.ptr[i] += B.step;
-            }
+            for (int i = 0; i < 4; ++i) load_to_lds_16(B.base, B.off[i], dsta + kOperandBytes + i * 4096);
+            B.base += B.step;
         }
     }
     if (KT >= kDist) wait_vmcnt<8 * (kDist - 1)>();   // the first tile is in
@@ -313,18 +302,29 @@ __device__ __forceinline__ void k_loop(Operand& A, Operand& B, int KT, unsigned 
         fa[0][i] = read_frag<E, AKM>(lds, g.a_rd, g.a_km, g.e6, g.cx16, i, 0);
         fb[0][i] = read_frag<E, BKM>(lds, g.b_rd, g.b_km, g.e6, g.cx16, i, 0);
     }
-    int st = 0, fill = kDist;
     int kt = 0;
-    for (; kt + kDist < KT; ++kt) {   // tile kt + kDist goes into the stage consumed in the previous iteration
+    // Four k-tiles per trip, one per stage of the ring, so that every stage address in the body is a constant
+    // (the tile multiplied sits in stage s, the one requested goes into stage s - 1, consumed in the previous
+    // step): LDS read addresses then need no arithmetic in the loop.
+    for (; kt + kDist + kStages <= KT; kt += kStages) {
+#pragma unroll
+        for (int st = 0; st < kStages; ++st) {
+            const int stn = (st + 1) % kStages, fill = (st + kDist) % kStages;
+            k_step<E, AKM, BKM, true>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes, wave_lds + fill * kStageBytes,
+                                      g, fa, fb, acc);
+        }
+    }
+    int st = 0;
+    for (; kt + kDist < KT; ++kt) {   // what is left of the tiles that still request one
         const int stn = (st + 1 == kStages) ? 0 : st + 1;
-        k_step<E, AKM, BKM, true>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes,
-                                  wave_base + fill * kStageBytes, wave_lds + fill * kStageBytes, g, fa, fb, acc);
+        const int fill = (st + kDist) % kStages;
+        k_step<E, AKM, BKM, true>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes, wave_lds + fill * kStageBytes, g,
+                                  fa, fb, acc);
         st = stn;
-        fill = (fill + 1 == kStages) ? 0 : fill + 1;
     }
     for (; kt < KT; ++kt) {           // the last tiles: nothing left to request
         const int stn = (st + 1 == kStages) ? 0 : st + 1;
-        k_step<E, AKM, BKM, false>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes, nullptr, 0u, g, fa, fb, acc);
+        k_step<E, AKM, BKM, false>(A, B, lds + st * kStageBytes, lds + stn * kStageBytes, 0u, g, fa, fb, acc);
         st = stn;
     }
     wait_lgkmcnt0();
