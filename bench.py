@@ -25,10 +25,10 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
 # Kernel names as rocprofv3 prints them, demangled or mangled, matched exactly (template arguments
 # included: the selector-stress launch is select_kernel<32, 8>, not the other group sizes' variants).
 KERNEL_SYMBOLS = {"token loss forward": (r"::fwd_kernel\(", r"\d+fwd_kernelE"),
-                  "token loss rescale": (r"::rescale_kernel\(", r"\d+rescale_kernelE"),
+                  "token loss normalise": (r"::rescale_kernel\(", r"\d+rescale_kernelE"),
                   "token loss d_hidden": (r"::dh_kernel\(", r"\d+dh_kernelE"),
                   "token loss d_w_lm": (r"::dw_kernel\(", r"\d+dw_kernelE"),
-                  "pods_select": (r"::select_kernel<32, 8>\(", r"\d+select_kernelILi32ELi8EE")}
+                  "pods_select": (r"::select_quarter_kernel<64>\(", r"\d+select_quarter_kernelILi64EE")}
 PROBE_BYTES = 1 << 30         # the calibration copy reads and writes this many bytes
 
 

@@ -187,7 +187,7 @@ pods_status pods_downsample_gather(const float* rewards, const uint32_t* rand_ke
 
 /* Bytes of workspace grpo_token_loss_fwd_bwd wants for these sizes (a recommendation: any
  * workspace of at least grpo_token_loss_workspace_min_bytes works; below the recommendation the
- * backward pass uses smaller vocabulary chunks, above it nothing changes).  Returns 0 for invalid
+ * call works through the tokens in smaller blocks, above it nothing changes).  Returns 0 for invalid
  * sizes. */
 size_t grpo_token_loss_workspace_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
 size_t grpo_token_loss_workspace_min_bytes(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt);
@@ -223,8 +223,10 @@ size_t grpo_token_loss_workspace_used_bytes(int32_t R, int32_t T, int32_t d, int
  *   workspace 256-byte aligned device buffer of workspace_bytes; contents undefined after the call
  *
  * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; softmax statistics are
- * fp32.  For the two gradient contractions the softmax part of the per-logit gradient is rounded
- * to fp16 (scaled so that it cannot overflow), the weight and the token-weighted hidden state are
+ * fp32.  The logits are computed once: the forward pass keeps the softmax numerators of one block of
+ * tokens at a time in the workspace (fp16, under power-of-two scales so that they cannot overflow), and
+ * the backward pass reads them.  For the two gradient contractions the softmax part of the per-logit
+ * gradient is thus rounded to fp16, the weight and the token-weighted hidden state are
  * copied to fp16 under power-of-two scales taken from their largest magnitudes (exact for elements
  * within 2^22 of the largest, see pods_loss_report), and the generated token's own logit is applied
  * in fp32; results are deterministic (no floating-point atomics).  A bf16 call with d not a multiple
@@ -328,8 +330,8 @@ pods_status grpo_token_loss_report(const void* workspace, pods_loss_report* repo
  * in a device array built into the library, PODS_STATIC_WORKSPACE_BYTES per GPU, which every GPU the
  * library runs on holds until the process ends.  The call allocates and frees nothing.  Sizes whose
  * minimal workspace (grpo_token_loss_workspace_min_bytes) exceeds that array are rejected with
- * PODS_ERR_UNSUPPORTED before anything is launched.  Within the array the call picks its vocabulary
- * chunk as grpo_token_loss_fwd_bwd does for a workspace of that size, so the results are those of that
+ * PODS_ERR_UNSUPPORTED before anything is launched.  Within the array the call picks its token block
+ * as grpo_token_loss_fwd_bwd does for a workspace of that size, so the results are those of that
  * call.  The array belongs to the GPU that is current when the call is made; all calls on one GPU share
  * it, so two calls that overlap in time on the same GPU (different streams or threads) race: serialise
  * them.  Each call writes every part of the array it later reads; nothing is kept between calls.
