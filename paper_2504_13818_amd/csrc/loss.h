@@ -102,7 +102,7 @@ struct LossPlan {
                       // power of two apart
     int64_t vld;      // V rounded up to kTile: rows of the fp16 weight copy, columns of the transposed one
     int loss_blocks;
-    size_t off_hdr, off_gmax, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_cscale, off_pmax,
+    size_t off_hdr, off_gmax, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_cscale, off_efix, off_pmax,
         off_psum, off_qscale, off_losspart, off_wtt, off_htt, off_wt, off_ht, off_dz, total;
 };
 

@@ -27,6 +27,8 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     p.off_g = take(sizeof(float) * (size_t)p.ncap_ld);
     p.off_coef = take(sizeof(float) * (size_t)p.ncap_ld);
     p.off_cscale = take(sizeof(float) * (size_t)p.ncap_ld);
+    // matrix-core path: the exponent a token's vocabulary tiles agree on after the first forward launch
+    p.off_efix = take(p.mfma ? sizeof(float) * (size_t)p.ncap_ld : 0);
     p.off_pmax = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
     p.off_psum = take(sizeof(float) * (size_t)p.ncap_ld * p.slots);
     // matrix-core path: fp16 power-of-two factor per (vocabulary tile, token) of the softmax numerators
@@ -178,9 +180,10 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
 // BASE2 = false (plain path): a partial is (m, sum exp(z - m)).
 // BASE2 = true (matrix-core path): a partial is (E, sum exp(z) 2^-E) with E an integer, so partials combine
 // by exact powers of two; besides lse the kernel writes, for the softmax numerators 2^14 exp(z) 2^-E kept by
-// the forward pass: cscale[p] = 2^Eref exp(-lse) in [1, 2) with Eref = ceil(lse log2 e), and
-// qscale[tile][p] = 2^(E - Eref) <= 1 in fp16 (exact; 0 below 2^-24), so that
-// 2^14 softmax = numerator * qscale * cscale.
+// the forward pass: Eref = the largest E among the token's tiles, cscale[p] = 2^Eref exp(-lse) (at most 8, at
+// least 1/V: the largest logit lies within 3 binades below 2^Eref), and qscale[tile][p] = 2^(E - Eref) <= 1
+// in fp16 (exact; 0 below 2^-24), so that 2^14 softmax = numerator * qscale * cscale.  Every tile that
+// already used Eref, which after the first forward launch of a token block is the rule, has qscale = 1.
 template <bool BASE2>
 __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__ hdr,
                                                   const float* __restrict__ pmax,
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__
                 Lt += BASE2 ? ldexpf(sl[i][lane], (int)(sm[i][lane] - Mt)) : sl[i][lane] * expf(sm[i][lane] - Mt);
         if constexpr (BASE2) {
             const float lse2 = Mt + log2f(Lt);
-            eref = ceilf(lse2);
+            eref = Mt;
             if (w == 0) {
                 lse_out[p] = lse2 * 0.6931471805599453f;
                 cscale[p] = exp2f(eref - lse2);

@@ -7,18 +7,23 @@
 // range):
 //
 //   forward    z[v][t]  = sum_k Wt[k][v]  Ht[k][t]      -> per token and vocabulary tile: an integer E with
-//                                                          2^E >= exp(max z), sum exp(z) 2^-E, z_y, and the
+//                                                          2^(E+2) > exp(max z), sum exp(z) 2^-E, z_y, and the
 //                                                          numerators 2^14 exp(z) 2^-E as fp16
-//   normalise  q[t][v]  = numerator * 2^(E - Eref_t)    -> q = 2^14 softmax / c_t (0 at v = y), in place, exact
+//   normalise  q[t][v]  = numerator * 2^(E - Eref_t)    -> q = 2^14 softmax / c_t (0 at v = y), in place, exact;
+//                                                          only where E differs from Eref_t = max E of the token
 //   d_hidden   dH[k][t] = sum_v W16[v][k] q[t][v]       -> times -g_t, over the whole vocabulary
 //   d_w_lm     dW[k][v] = sum_t H16[t][k] q[t][v]       -> accumulated over the token blocks
 //
 // The softmax numerators of ONE token block, q[nb][V], are the only [tokens, vocabulary]-shaped array that
 // ever exists (10 GB of the 90 GB the full logits would take at the Qwen2.5-3B-shaped sizes): keeping them
-// from the forward pass, under a per-tile power-of-two offset that a cheap elementwise pass takes out once
-// the log-sum-exp is known (the remaining per-token factor c_t in [1, 2) rides on the token's weight g_t),
-// spares the backward pass a second logits contraction (2 N d V of the 8 N d V
-// floating-point operations a recomputing backward pass executes).
+// from the forward pass, under a power-of-two offset per (token, vocabulary tile), spares the backward pass a
+// second logits contraction (2 N d V of the 8 N d V floating-point operations a recomputing backward pass
+// executes).  After a block's first forward launch (the first 8192 vocabulary columns) every token fixes the
+// exponent its later tiles use: two above the larger of the first launch's exponents and that of the generated
+// token's own logit, which a policy that sampled the token has made large.  A tile takes the agreed exponent
+// unless its own lies two or more above it, so for nearly every token all later tiles share one offset and the
+// normalising pass has only the first launch's tiles (and such rare tokens) to touch; the remaining per-token
+// factor c_t = 2^Eref exp(-lse) rides on the token's weight g_t.
 //
 // An operand whose contraction index is its row index in memory (all of them except q in
 // d_hidden) is staged in LDS as it lies in memory and read with the transposing LDS load, so q is
@@ -348,13 +353,15 @@ __device__ __forceinline__ int acc_slot_of(int rel) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Forward: one workgroup per (token tile, vocabulary tile).  Per token: E = the smallest integer with
-// 2^E >= exp(largest logit of the tile), the sum of exp(z) 2^-E over the tile (one partial per vocabulary
-// tile, merged later by the log-sum-exp kernel), z_y, and the tile's softmax numerators 2^14 exp(z) 2^-E
-// rounded to fp16 (0 at v = y and past V), token-major, into the block's q array.  E is common to the tile's
-// two vocabulary waves (exchanged through LDS).  Once the token's log-sum-exp is known, the numerators are
-// 2^14 softmax up to one power of two per (token, vocabulary tile), which the normalising pass applies (exact
-// in fp16), and one factor in [1, 2) per token, which the gradient kernels get with the token's weight.
+// Forward: one workgroup per (token tile, vocabulary tile).  Per token: an integer exponent E (without
+// `efix`, the smallest with 2^E >= exp(largest logit of the tile); with it, the token's agreed exponent
+// efix[p] unless the tile's own lies two or more above), the sum of exp(z) 2^-E over the tile (one partial per
+// vocabulary tile, merged later by the log-sum-exp kernel), z_y, and the tile's softmax numerators
+// 2^14 exp(z) 2^-E <= 2^15 rounded to fp16 (0 at v = y and past V), token-major, into the block's q array.
+// E is common to the tile's two vocabulary waves (exchanged through LDS).  Once the token's log-sum-exp is
+// known, the numerators are 2^14 softmax up to one power of two per (token, vocabulary tile), which the
+// normalising pass applies where it is not 1 (exact in fp16), and one factor per token, which the gradient
+// kernels get with the token's weight.
 // One tile per workgroup (rather than a workgroup walking many vocabulary tiles) keeps the 32
 // workgroups of an XCD in step, which is what lets them share operand tiles in the 4 MiB L2.
 // A launch covers the token tiles of one token block (first row row0) and vocabulary tiles
@@ -363,7 +370,8 @@ __device__ __forceinline__ int acc_slot_of(int rel) {
 template <bool PARTIAL>
 __device__ __forceinline__ void fwd_epilogue(const f32x16 (&acc)[4][4], const LaneGeom& g, unsigned char* lds,
                                              const int32_t* __restrict__ tok, int64_t n_valid, int64_t gt,
-                                             int64_t vt, int V, int64_t slot_stride, float* __restrict__ pmax,
+                                             int64_t vt, int V, int64_t slot_stride,
+                                             const float* __restrict__ efix, float* __restrict__ pmax,
                                              float* __restrict__ psum, float* __restrict__ zy,
                                              _Float16* __restrict__ qtile, int64_t ldq) {
     const int vtile = g.wm * 128 + 4 * (g.lane >> 5);        // tile-local vocabulary row of (mi=0, r=0)
@@ -392,7 +400,13 @@ __device__ __forceinline__ void fwd_epilogue(const f32x16 (&acc)[4][4], const La
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {   // the tile holds at least one vocabulary row, so this is finite
         const float m = fmaxf(Mt[ni], red_max[(g.wm ^ 1) * kTile + g.wn * 128 + ni * 32 + (g.lane & 31)]);
-        Mt[ni] = ceilf(m * kLog2e);    // the tile's reference exponent E: an integer, 2^E >= exp(m) > 2^(E-1)
+        float e = ceilf(m * kLog2e);   // the tile's own exponent: an integer, 2^e >= exp(m) > 2^(e-1)
+        if (efix != nullptr) {         // the token's agreed exponent serves unless this tile lies too far above it
+            const int64_t p = gt * kTile + g.wn * 128 + ni * 32 + (g.lane & 31);
+            const float ef = p < n_valid ? efix[p] : e;
+            if (e <= ef + 1.0f) e = ef;
+        }
+        Mt[ni] = e;                    // the tile's reference exponent E: exp(m) <= 2^(E+1)
     }
 
     // The q tile goes to memory through LDS: a lane holds 4 consecutive vocabulary entries of one token,
@@ -409,7 +423,7 @@ __device__ __forceinline__ void fwd_epilogue(const f32x16 (&acc)[4][4], const La
             const int tloc = g.wn * 128 + ni * 32 + (g.lane & 31);
             const int64_t p = gt * kTile + tloc;
             const bool valid = p < n_valid;
-            // kQScale exp(z) 2^-E = 2^(z log2e - E + 14), at most 2^14; rows past N get 2^-inf = 0
+            // kQScale exp(z) 2^-E = 2^(z log2e - E + 14), at most 2^15; rows past N get 2^-inf = 0
             const float off = valid ? kLog2Q - Mt[ni] : -__builtin_huge_valf();
             unsigned char* row = lds + tloc * kQPitch + vtile * 2;
             float sum = 0.0f;
@@ -483,6 +497,7 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
                                                      const uint16_t* __restrict__ wt,
                                                      int d, int V, int vt0, int nvt_launch, int64_t row0,
                                                      int ntt_grid, int64_t slot_stride,
+                                                     const float* __restrict__ efix,
                                                      float* __restrict__ pmax, float* __restrict__ psum,
                                                      float* __restrict__ zy, int64_t ldq,
                                                      _Float16* __restrict__ q) {
@@ -506,32 +521,88 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
     __builtin_amdgcn_s_barrier();                 // every wave has left the operand ring
     _Float16* qtile = q + (tt * kTile) * ldq + vt * kTile;
     if ((int)vt * kTile + kTile > V)              // last vocabulary tile: rows >= V do not exist
-        fwd_epilogue<true>(acc, g, lds, tok, n_valid, gt, vt, V, slot_stride, pmax, psum, zy, qtile, ldq);
+        fwd_epilogue<true>(acc, g, lds, tok, n_valid, gt, vt, V, slot_stride, efix, pmax, psum, zy, qtile, ldq);
     else
-        fwd_epilogue<false>(acc, g, lds, tok, n_valid, gt, vt, V, slot_stride, pmax, psum, zy, qtile, ldq);
+        fwd_epilogue<false>(acc, g, lds, tok, n_valid, gt, vt, V, slot_stride, efix, pmax, psum, zy, qtile, ldq);
+}
+
+// ------------------------------------------------------------------------------------------
+// The exponent a token's vocabulary tiles agree on, fixed after the block's first forward launch: two above the
+// larger of (a) the exponents of that launch's `slots0` tiles and (b) that of the generated token's own logit
+// z_y = h_t . W_y (fp32 dot product of the bf16 rows; only its binade matters here).  One wave per token.
+// ------------------------------------------------------------------------------------------
+constexpr float kExponentMargin = 2.0f;
+__global__ __launch_bounds__(256) void exponent_kernel(const LossHeader* __restrict__ hdr,
+                                                       const int32_t* __restrict__ row_map,
+                                                       const int32_t* __restrict__ tok,
+                                                       const uint16_t* __restrict__ hidden,
+                                                       const uint16_t* __restrict__ w, int d,
+                                                       const float* __restrict__ pmax, int slots0,
+                                                       int64_t slot_stride, int64_t row0, int64_t row_end,
+                                                       float* __restrict__ efix) {
+    const int lane = threadIdx.x & 63;
+    const int64_t p = row0 + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= hdr->n_valid || p >= row_end) return;
+    const uint16_t* h = hidden + (int64_t)row_map[p] * d;
+    const uint16_t* wy = w + (int64_t)tok[p] * d;
+    float dot = 0.0f;
+    for (int k = lane * 8; k < d; k += 512) {
+        const u32x4 x = *reinterpret_cast<const u32x4*>(h + k);
+        const u32x4 y = *reinterpret_cast<const u32x4*>(wy + k);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            dot = fmaf(__uint_as_float(x[j] << 16), __uint_as_float(y[j] << 16), dot);
+            dot = fmaf(__uint_as_float(x[j] & 0xFFFF0000u), __uint_as_float(y[j] & 0xFFFF0000u), dot);
+        }
+    }
+    float m = -__builtin_huge_valf();
+    for (int s = lane; s < slots0; s += 64) m = fmaxf(m, pmax[s * slot_stride + p]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        dot += __shfl_xor(dot, o, 64);
+        m = fmaxf(m, __shfl_xor(m, o, 64));
+    }
+    if (lane == 0) efix[p] = fmaxf(m, ceilf(dot * kLog2e)) + kExponentMargin;
 }
 
 // ------------------------------------------------------------------------------------------
 // Normalise (per token block, once its log-sum-exp is known): the forward pass's numerators times the power
 // of two of their (token, vocabulary tile), in place: exact in fp16 (results below 2^-24 vanish).  Afterwards
-// q = 2^14 softmax / c_t with the per-token factor c_t in [1, 2) that rides on the token's weight.
-// 16 bytes per lane; bound by HBM (2 x 2 bytes per logit of the block).
+// q = 2^14 softmax / c_t with the per-token factor c_t that rides on the token's weight.  A factor of 1
+// (the tile was written under the token's final exponent) leaves the tile untouched.  One workgroup per
+// (8 vocabulary tiles, 32 token rows): it leaves at once when all its 256 factors are 1; otherwise it walks its
+// rows, 16 bytes per lane and 4 KiB contiguous per row.  Bound by HBM (2 x 2 bytes per logit it touches).
 // ------------------------------------------------------------------------------------------
+constexpr int kRescaleRows = 32;
 __global__ __launch_bounds__(256) void rescale_kernel(const LossHeader* __restrict__ hdr,
                                                       const _Float16* __restrict__ qscale, int64_t slot_stride,
-                                                      int64_t row0, int granules, int64_t ldq,
+                                                      int64_t row0, int ntiles, int64_t ldq,
                                                       _Float16* __restrict__ q) {
-    const int64_t r = blockIdx.y;
-    const int64_t p = row0 + r;
-    if (p >= hdr->n_bwd) return;
-    const int gcol = blockIdx.x * 256 + threadIdx.x;
-    if (gcol >= granules) return;
-    const _Float16 s = qscale[(int64_t)(gcol >> 5) * slot_stride + p];   // 32 granules of 8 per vocabulary tile
-    _Float16* at = q + r * ldq + (int64_t)gcol * 8;
-    f16x8 x = *reinterpret_cast<const f16x8*>(at);
+    __shared__ _Float16 sc[8][kRescaleRows];
+    const int64_t r0 = (int64_t)blockIdx.y * kRescaleRows;
+    const int64_t n_bwd = hdr->n_bwd;
+    if (row0 + r0 >= n_bwd) return;
+    const int tile0 = blockIdx.x * 8;
+    {
+        const int tl = threadIdx.x >> 5, rl = threadIdx.x & 31;      // 8 tiles x 32 rows
+        _Float16 s = (_Float16)1.0f;
+        if (tile0 + tl < ntiles && row0 + r0 + rl < n_bwd) s = qscale[(int64_t)(tile0 + tl) * slot_stride + row0 + r0 + rl];
+        sc[tl][rl] = s;
+        if (__syncthreads_or(s != (_Float16)1.0f) == 0) return;
+    }
+    const int tl = threadIdx.x >> 5;                                 // 32 granules of 8 per vocabulary tile
+    if (tile0 + tl >= ntiles) return;
+    _Float16* at = q + r0 * ldq + (int64_t)tile0 * kTile + (int64_t)threadIdx.x * 8;
+#pragma unroll 4
+    for (int r = 0; r < kRescaleRows; ++r) {
+        const _Float16 s = sc[tl][r];
+        if (s != (_Float16)1.0f) {
+            f16x8 x = *reinterpret_cast<const f16x8*>(at + r * ldq);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) x[j] = x[j] * s;
-    *reinterpret_cast<f16x8*>(at) = x;
+            for (int j = 0; j < 8; ++j) x[j] = x[j] * s;
+            *reinterpret_cast<f16x8*>(at + r * ldq) = x;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -877,6 +948,7 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
     auto* h16 = reinterpret_cast<_Float16*>(ws + p.off_ht);
     auto* q = reinterpret_cast<_Float16*>(ws + p.off_dz);
     auto* qscale = reinterpret_cast<const _Float16*>(ws + p.off_qscale);
+    auto* efix = reinterpret_cast<float*>(ws + p.off_efix);
     const auto* hidden = static_cast<const uint16_t*>(a.hidden);
     const auto* w = static_cast<const uint16_t*>(a.w_lm);
     pods_status st;
@@ -900,7 +972,6 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
     const int64_t nvt = p.vld / kTile;
     const int64_t dt256 = ceil_div(a.d, kTile);
     const int64_t step_vt = kDefaultVocabChunk / kTile;
-    const int granules = (int)(p.vld / 8);
     for (int b = 0; b < p.nblocks; ++b) {
         const int64_t row0 = (int64_t)b * p.nb;
         const int64_t rows = p.ncap_ld - row0 < p.nb ? p.ncap_ld - row0 : p.nb;   // capacity of this block
@@ -912,12 +983,19 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
             PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nl)),
                         dim3(256), kFwdLdsBytes, a.stream, hdr, tok, reinterpret_cast<const uint16_t*>(ht),
                         reinterpret_cast<const uint16_t*>(wt), a.d, a.V, (int)vt0, (int)nl, row0, (int)ntt,
-                        p.ncap_ld, pmax, psum, zy, p.ldq, q);
+                        p.ncap_ld, vt0 == 0 ? static_cast<const float*>(nullptr) : efix, pmax, psum, zy, p.ldq, q);
             if ((st = check_launch("token loss forward")) != PODS_OK) return st;
+            if (vt0 == 0 && nl < nvt) {   // later launches write under the exponent each token fixes now
+                PODS_LAUNCH("token loss exponent", a.stream, exponent_kernel, dim3((unsigned)ceil_div(rows, 4)), dim3(256),
+                            0, a.stream, hdr, row_map, tok, hidden, w, a.d, pmax, (int)nl, p.ncap_ld, row0, row0 + rows,
+                            efix);
+                if ((st = check_launch("token loss exponent")) != PODS_OK) return st;
+            }
         }
         if ((st = launch_surrogate(a, p, row0, rows, b)) != PODS_OK) return st;
-        PODS_LAUNCH("token loss normalise", a.stream, rescale_kernel, dim3((unsigned)ceil_div(granules, 256), (unsigned)rows),
-                    dim3(256), 0, a.stream, hdr, qscale, p.ncap_ld, row0, granules, p.ldq, q);
+        PODS_LAUNCH("token loss normalise", a.stream, rescale_kernel,
+                    dim3((unsigned)ceil_div(nvt, 8), (unsigned)ceil_div(rows, kRescaleRows)), dim3(256), 0, a.stream, hdr,
+                    qscale, p.ncap_ld, row0, (int)nvt, p.ldq, q);
         if ((st = check_launch("token loss normalise")) != PODS_OK) return st;
         PODS_LAUNCH("convert H", a.stream, convert_kernel, dim3((unsigned)ceil_div(rows * per_row, 256)), dim3(256), 0,
                     a.stream, hdr, gmax + b, row_map, g, hidden, row0, rows, (int64_t)0, a.d, 1, h16);
