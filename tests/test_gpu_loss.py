@@ -81,3 +81,39 @@ def test_bf16_full_head_reduced_tokens(pods, cfg, R, T):
     case = H.loss_case(cfg, R, T, c["d"], c["V"], sigma=0.05)
     scale = float(R * case["lengths"].mean())
     H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale))
+
+
+def test_bf16_peaked_logits_beyond_the_first_forward_launch(pods):
+    """A vocabulary of three forward launches (8192 columns each) where some tokens have one logit about 15 nats
+    above the rest, sitting in the second or third launch.  For half of them it is the generated token's own
+    logit (the exponent the token's tiles agree on after the first launch then already covers it); for the
+    other half it is another row (that row's tile lies far above the agreed exponent, keeps its own, and every
+    other tile of the token is brought down to it afterwards, most of its numerators into fp16's subnormal
+    range or to zero).  Both must match the oracle like any other case."""
+    from oracle import pods_oracle as po
+    cfg, R, T, d, V = 1, 6, 100, 256, 20000
+    c = inputs.CONFIGS[cfg]
+    h, w = inputs.dense(cfg, R, T, d, V)
+    tok = inputs.tokens(cfg, R, T, V)
+    lens = inputs.lengths(cfg, R, T)
+    rng = np.random.default_rng(77)
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    hot_rows = rng.choice(np.arange(8192, V), size=24, replace=False)
+    w[hot_rows] += 0.5 * u                                       # z rises by 0.5 * beta at the hot rows
+    peaked = rng.random((R, T)) < 0.4
+    h[peaked] += 30.0 * u                                        # ... by about 15 nats for these tokens
+    own = peaked & (rng.random((R, T)) < 0.5)
+    tok[own] = rng.choice(hot_rows, size=int(own.sum())).astype(tok.dtype)
+    h = inputs.bf16_bits_to_f32(inputs.f32_to_bf16_bits(h))
+    w = inputs.bf16_bits_to_f32(inputs.f32_to_bf16_bits(w))
+    adv = H.oracle_adv(cfg, R)
+    cur = po.grpo_token_loss(h, w, tok, np.zeros((R, T), np.float32), adv, lens, c["clip_eps"],
+                             want_dw=False)["logp"]
+    valid = np.arange(T)[None, :] < lens[:, None]
+    assert (cur[valid & own] > -6.0).mean() > 0.9 and (cur[valid & peaked & ~own] < -8.0).mean() > 0.9
+    case = dict(cfg=cfg, hidden=h, w=w, tokens=tok, lengths=lens, adv=adv,
+                old_logp=inputs.old_logp_from(cur, cfg, 0.2), clip_eps=c["clip_eps"], dtype="bf16")
+    H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case))
+    scale = float(R * lens.mean())
+    H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale))

@@ -1,8 +1,8 @@
-"""Elementwise oracle parity where the three token-tiled matrix-core kernels take the tile mapping the
+"""Elementwise oracle parity where the token-tiled matrix-core kernels take the tile mapping the
 benchmark shapes run: a token-tile capacity of 512 (R = 128 rollouts x T = 1024, about 290 tiles of valid
-tokens), so that the forward / recompute launches (32 and 15 vocabulary tiles) and the d_hidden launches
+tokens), so that the forward launches (32 and 15 vocabulary tiles) and the d_hidden launches
 (8 d-tiles at d = 2048, as in the Qwen2.5-3B-shaped config) all have at least 64 blocks of tiles, and a
-vocabulary of two chunks with a ragged last tile.  Every element of logp, d_hidden and d_w_lm is
+vocabulary of two forward launches with a ragged last tile.  Every element of logp, d_hidden and d_w_lm is
 compared with the CPU oracle, at the natural scale of the loss (the plain 2e-3 / 1e-4 bar) and at unit
 scale (d_w_lm there with the rounding allowance its fp16 operands call for)."""
 import numpy as np
