@@ -709,14 +709,17 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
                                                     const uint16_t* __restrict__ h16,
                                                     const uint16_t* __restrict__ q, int64_t ldq,
                                                     int d, int V, int64_t row0, int64_t nb, int first_block,
-                                                    int accumulate, float* __restrict__ d_w) {
+                                                    int accumulate, int64_t wg0, float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
     int64_t n_rows = hdr->n_bwd - row0;               // rows of this block that take part
     n_rows = n_rows < 0 ? 0 : (n_rows > nb ? nb : n_rows);
     if (n_rows == 0 && !first_block) return;          // nothing to add
     const int64_t vround = ((int64_t)V + kTile - 1) / kTile * kTile;
     int64_t vt, kt0;
-    if (!decode_tile(blockIdx.x, vround / kTile, (d + kTile - 1) / kTile, vt, kt0)) return;
+    const int64_t nvt = vround / kTile, ndt = (d + kTile - 1) / kTile;
+    if (use_strips(nvt) ? !decode_strip_tile(wg0 + blockIdx.x, nvt, ndt, vt, kt0)
+                        : !decode_tile(wg0 + blockIdx.x, nvt, ndt, vt, kt0))
+        return;
     const LaneGeom g = lane_geom();
 
     Operand A, B;
@@ -1007,10 +1010,17 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
                     kDhLdsBytes, a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
                     reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, (int)ntt, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
-        PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)super_grid_blocks(nvt, dt256)), dim3(256),
-                    kLdsBytes, a.stream, hdr, gmax + b, reinterpret_cast<const uint16_t*>(h16),
-                    reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, rows, b == 0 ? 1 : 0,
-                    (a.accumulate_d_w || b > 0) ? 1 : 0, a.d_w_lm);
+        // With many vocabulary tiles: one launch per round of the chip (see decode_strip_tile).
+        const bool strips = use_strips(nvt);
+        const int64_t dw_total = strips ? strip_grid_blocks(nvt, dt256) : super_grid_blocks(nvt, dt256);
+        const int64_t dw_round = strips ? kRoundWorkgroups : dw_total;
+        for (int64_t wg0 = 0; wg0 < dw_total; wg0 += dw_round) {
+            const int64_t nwg = dw_total - wg0 < dw_round ? dw_total - wg0 : dw_round;
+            PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)nwg), dim3(256),
+                        kLdsBytes, a.stream, hdr, gmax + b, reinterpret_cast<const uint16_t*>(h16),
+                        reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, rows, b == 0 ? 1 : 0,
+                        (a.accumulate_d_w || b > 0) ? 1 : 0, wg0, a.d_w_lm);
+        }
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;
     }
     PODS_LAUNCH("token loss d_w_lm (y logit)", a.stream, dw_onehot_kernel, dim3((unsigned)ceil_div(a.V, 4 * kOnehotRows)), dim3(256), 0,

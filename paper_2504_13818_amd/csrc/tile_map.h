@@ -63,4 +63,27 @@ PODS_HOST_DEVICE inline bool decode_tile(int64_t bid, int64_t n0, int64_t n1, in
     return st < nst && t0 < n0 && t1 < n1;
 }
 
+// d_w_lm's mapping for tile grids with many tiles on the first axis (the vocabulary): the workgroups of an XCD
+// walk strips of 4 x n1 tiles, the first axis fastest inside a strip, strips going round the XCDs.  Any 32
+// consecutive workgroups of an XCD then cover 4 x 8 tiles (or the end of one strip and the start of the XCD's
+// next) whatever n1 is, and the host launches kRoundWorkgroups ids at a time: one workgroup per compute unit,
+// all started together, so that those 32 walk the contraction axis in step and share operand tiles in the L2.
+// (Inside one long launch the workgroups of a block start as compute units fall free, drift apart by more than
+// the L2 holds, and fetch most operand tiles once each.)
+constexpr int64_t kRoundWorkgroups = 256;
+PODS_HOST_DEVICE inline bool use_strips(int64_t n0) { return (n0 + kSuper0 - 1) / kSuper0 >= kFewBlocks; }
+PODS_HOST_DEVICE inline int64_t strip_grid_blocks(int64_t n0, int64_t n1) {
+    const int64_t strips = (n0 + kSuper0 - 1) / kSuper0;
+    return (strips + kXcds - 1) / kXcds * kXcds * kSuper0 * n1;
+}
+PODS_HOST_DEVICE inline bool decode_strip_tile(int64_t bid, int64_t n0, int64_t n1, int64_t& t0, int64_t& t1) {
+    const int64_t xcd = bid % kXcds, s = bid / kXcds;   // workgroup ids go round the XCDs
+    const int64_t per_strip = kSuper0 * n1;
+    const int64_t strip = (s / per_strip) * kXcds + xcd;
+    const int64_t w = s % per_strip;
+    t0 = strip * kSuper0 + w % kSuper0;
+    t1 = w / kSuper0;
+    return t0 < n0;
+}
+
 }  // namespace pods

@@ -23,6 +23,10 @@ def harness(tmp_path_factory):
     lib.tile_map_check_ids.argtypes = [i64, i64, i64]
     lib.tile_map_check_range.argtypes = [i64, i64, i64, i64, ctypes.POINTER(i64)]
     lib.tile_map_check_range.restype = i64
+    lib.strip_map_check_one.argtypes = [i64, i64]
+    lib.strip_map_check_range.argtypes = [i64, i64, i64, i64, ctypes.POINTER(i64)]
+    lib.strip_map_check_range.restype = i64
+    lib.strip_map_used.argtypes = [i64]
     for name in ("tile_map_blocks", "tile_map_grid"):
         getattr(lib, name).argtypes = [i64, i64]
         getattr(lib, name).restype = i64
@@ -67,3 +71,16 @@ def test_the_check_sees_a_broken_launch(harness):
         assert harness.tile_map_check_ids(n0, n1, grid) == 0
         assert harness.tile_map_check_ids(n0, n1, grid - 8) == 3
         assert harness.tile_map_check_ids(n0, n1, grid - 3) == 4
+
+
+def test_strip_mapping_of_d_w_lm(harness):
+    """d_w_lm with many vocabulary tiles (n0) launches one round of 256 workgroup ids at a time under its own
+    mapping: every tile exactly once, and the 32 workgroups an XCD gets in a round stay within 16 operand
+    columns.  Vocabulary tiles up to 1100 (V = 281 600) x d-tiles up to 64 (d = 16384)."""
+    first = (ctypes.c_int64 * 3)(0, 0, 0)
+    bad = harness.strip_map_check_range(1, 1100, 1, 64, first)
+    assert bad == 0, f"{bad} grids fail; first: n0={first[0]} n1={first[1]} code={first[2]}"
+    # the benchmark heads (594 and 501 vocabulary tiles) take this mapping, small vocabularies the general one
+    assert harness.strip_map_used(594) == 1 and harness.strip_map_used(501) == 1 and harness.strip_map_used(40) == 0
+    for n0, n1 in ((594, 8), (594, 14), (501, 16)):
+        assert harness.strip_map_check_one(n0, n1) == 0
