@@ -175,8 +175,8 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
 }
 
 // Per valid token of the rows [row0, row_end): the forward pass's partials, one per vocabulary tile, merged
-// into log-sum-exp.  64 tokens per workgroup; the four waves take every fourth partial each (coalesced across
-// tokens, many loads in flight) and are merged through LDS.
+// into log-sum-exp.  64 tokens per workgroup; its 16 waves take every sixteenth partial each (coalesced across
+// tokens, many loads in flight) and are merged through LDS in a fixed order.
 // BASE2 = false (plain path): a partial is (m, sum exp(z - m)).
 // BASE2 = true (matrix-core path): a partial is (E, sum exp(z) 2^-E) with E an integer, so partials combine
 // by exact powers of two; besides lse the kernel writes, for the softmax numerators 2^14 exp(z) 2^-E kept by
@@ -184,21 +184,22 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
 // least 1/V: the largest logit lies within 3 binades below 2^Eref), and qscale[tile][p] = 2^(E - Eref) <= 1
 // in fp16 (exact; 0 below 2^-24), so that 2^14 softmax = numerator * qscale * cscale.  Every tile that
 // already used Eref, which after the first forward launch of a token block is the rule, has qscale = 1.
+constexpr int kLseWaves = 16;
 template <bool BASE2>
-__global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__ hdr,
+__global__ __launch_bounds__(64 * kLseWaves) void lse_kernel(const LossHeader* __restrict__ hdr,
                                                   const float* __restrict__ pmax,
                                                   const float* __restrict__ psum, int slots,
                                                   int64_t slot_stride, int64_t row0, int64_t row_end,
                                                   float* __restrict__ lse_out, float* __restrict__ cscale,
                                                   _Float16* __restrict__ qscale) {
-    __shared__ float sm[4][64], sl[4][64];
+    __shared__ float sm[kLseWaves][64], sl[kLseWaves][64];
     const int64_t n_valid = hdr->n_valid < row_end ? hdr->n_valid : row_end;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t p = row0 + (int64_t)blockIdx.x * 64 + lane;
     float M = -__builtin_huge_valf(), L = 0.0f;
     if (p < n_valid) {
 #pragma unroll 4
-        for (int s = w; s < slots; s += 4) {
+        for (int s = w; s < slots; s += kLseWaves) {
             const float m = pmax[s * slot_stride + p];
             const float l = psum[s * slot_stride + p];
             if (m > -__builtin_huge_valf()) {
@@ -213,11 +214,13 @@ __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__
     sl[w][lane] = L;
     __syncthreads();
     float eref = 0.0f;
-    if (p < n_valid) {   // every wave merges the four partial results the same way
-        const float Mt = fmaxf(fmaxf(sm[0][lane], sm[1][lane]), fmaxf(sm[2][lane], sm[3][lane]));
+    if (p < n_valid) {   // every wave merges the waves' partial results the same way
+        float Mt = sm[0][lane];
+#pragma unroll
+        for (int i = 1; i < kLseWaves; ++i) Mt = fmaxf(Mt, sm[i][lane]);
         float Lt = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < kLseWaves; ++i)
             if (sm[i][lane] > -__builtin_huge_valf())
                 Lt += BASE2 ? ldexpf(sl[i][lane], (int)(sm[i][lane] - Mt)) : sl[i][lane] * expf(sm[i][lane] - Mt);
         if constexpr (BASE2) {
@@ -236,12 +239,12 @@ __global__ __launch_bounds__(256) void lse_kernel(const LossHeader* __restrict__
         // operands): their factors are zeros, not whatever the workspace held
         const int64_t tile_end = (hdr->n_valid + 255) / 256 * 256;
         if (p < n_valid) {
-            for (int s = w; s < slots; s += 4) {
+            for (int s = w; s < slots; s += kLseWaves) {
                 const float e = pmax[s * slot_stride + p];
                 qscale[s * slot_stride + p] = (_Float16)ldexpf(1.0f, (int)fmaxf(e - eref, -30.0f));
             }
         } else if (p >= hdr->n_valid && p < tile_end && p < row_end) {
-            for (int s = w; s < slots; s += 4) qscale[s * slot_stride + p] = (_Float16)0.0f;
+            for (int s = w; s < slots; s += kLseWaves) qscale[s * slot_stride + p] = (_Float16)0.0f;
         }
     }
 }
@@ -342,12 +345,12 @@ pods_status launch_surrogate(const LossArgs& a, const LossPlan& p, int64_t row0,
     unsigned char* ws = a.workspace;
     float* cscale = p.mfma ? reinterpret_cast<float*>(ws + p.off_cscale) : nullptr;
     if (p.mfma)
-        PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel<true>, dim3((unsigned)ceil_div(nrows, 64)), dim3(256), 0, a.stream,
+        PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel<true>, dim3((unsigned)ceil_div(nrows, 64)), dim3(64 * kLseWaves), 0, a.stream,
                     reinterpret_cast<const LossHeader*>(ws + p.off_hdr), reinterpret_cast<const float*>(ws + p.off_pmax),
                     reinterpret_cast<const float*>(ws + p.off_psum), p.slots, p.ncap_ld, row0, row0 + nrows,
                     reinterpret_cast<float*>(ws + p.off_lse), cscale, reinterpret_cast<_Float16*>(ws + p.off_qscale));
     else
-        PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel<false>, dim3((unsigned)ceil_div(nrows, 64)), dim3(256), 0, a.stream,
+        PODS_LAUNCH("log-sum-exp", a.stream, lse_kernel<false>, dim3((unsigned)ceil_div(nrows, 64)), dim3(64 * kLseWaves), 0, a.stream,
                     reinterpret_cast<const LossHeader*>(ws + p.off_hdr), reinterpret_cast<const float*>(ws + p.off_pmax),
                     reinterpret_cast<const float*>(ws + p.off_psum), p.slots, p.ncap_ld, row0, row0 + nrows,
                     reinterpret_cast<float*>(ws + p.off_lse), nullptr, nullptr);

@@ -796,31 +796,41 @@ __global__ __launch_bounds__(256) void dw_onehot_kernel(const LossHeader* __rest
     const int lane = threadIdx.x & 63;
     const int v_lo = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kOnehotRows;
     if (v_lo >= V) return;
-    for (int p0 = 0; p0 < n_valid; p0 += 64) {
-        const int p = p0 + lane;
-        const int y = (p < n_valid) ? tok[p] : -1;
-        unsigned long long hits = __ballot((unsigned)(y - v_lo) < (unsigned)kOnehotRows);
-        while (hits != 0ull) {
-            const int src = __ffsll((long long)hits) - 1;
-            hits &= hits - 1ull;
-            const int pp = p0 + src;
-            const int yy = __shfl(y, src, 64);
-            const float c = coef[pp];
-            if (c == 0.0f) continue;
-            const uint16_t* hrow = hidden + (int64_t)row_map[pp] * d;
-            float* out = d_w + (int64_t)yy * d;
-            for (int k = lane * 8; k < d; k += 512) {
-                const u32x4 raw = *reinterpret_cast<const u32x4*>(hrow + k);
-                f32x4 lo = *reinterpret_cast<f32x4*>(out + k);
-                f32x4 hi = *reinterpret_cast<f32x4*>(out + k + 4);
+    constexpr int kAhead = 8;     // token ids are fetched 8 x 64 at a time: the scan is bound by their latency
+    for (int q0 = 0; q0 < n_valid; q0 += 64 * kAhead) {
+        int ys[kAhead];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float e0 = __uint_as_float(raw[j] << 16), e1 = __uint_as_float(raw[j] & 0xFFFF0000u);
-                    if (j < 2) { lo[2 * j] += c * e0; lo[2 * j + 1] += c * e1; }
-                    else { hi[2 * j - 4] += c * e0; hi[2 * j - 3] += c * e1; }
+        for (int i = 0; i < kAhead; ++i) {
+            const int p = q0 + i * 64 + lane;
+            ys[i] = (p < n_valid) ? tok[p] : -1;
+        }
+#pragma unroll
+        for (int i = 0; i < kAhead; ++i) {
+            const int p0 = q0 + i * 64;
+            const int y = ys[i];
+            unsigned long long hits = __ballot((unsigned)(y - v_lo) < (unsigned)kOnehotRows);
+            while (hits != 0ull) {
+                const int src = __ffsll((long long)hits) - 1;
+                hits &= hits - 1ull;
+                const int pp = p0 + src;
+                const int yy = __shfl(y, src, 64);
+                const float c = coef[pp];
+                if (c == 0.0f) continue;
+                const uint16_t* hrow = hidden + (int64_t)row_map[pp] * d;
+                float* out = d_w + (int64_t)yy * d;
+                for (int k = lane * 8; k < d; k += 512) {
+                    const u32x4 raw = *reinterpret_cast<const u32x4*>(hrow + k);
+                    f32x4 lo = *reinterpret_cast<f32x4*>(out + k);
+                    f32x4 hi = *reinterpret_cast<f32x4*>(out + k + 4);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float e0 = __uint_as_float(raw[j] << 16), e1 = __uint_as_float(raw[j] & 0xFFFF0000u);
+                        if (j < 2) { lo[2 * j] += c * e0; lo[2 * j + 1] += c * e1; }
+                        else { hi[2 * j - 4] += c * e0; hi[2 * j - 3] += c * e1; }
+                    }
+                    *reinterpret_cast<f32x4*>(out + k) = lo;
+                    *reinterpret_cast<f32x4*>(out + k + 4) = hi;
                 }
-                *reinterpret_cast<f32x4*>(out + k) = lo;
-                *reinterpret_cast<f32x4*>(out + k + 4) = hi;
             }
         }
     }
