@@ -333,8 +333,8 @@ def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False,
 
 def context_numbers(lib, torch, dev, n_tokens, d, vc=8192):
     """Numbers measured in this process beside the token loss's own, as context for its fraction of the
-    published matrix-core peak (never the target): the vendor GEMM (torch.matmul, bf16) on the shape of one
-    d_w_lm launch, and a loop of matrix instructions with no memory traffic at all."""
+    published matrix-core peak (never the target): the vendor GEMM (torch.matmul, bf16) on the shape of
+    d_w_lm's contraction for 8192 vocabulary columns, and a loop of matrix instructions with no memory traffic at all."""
     import numpy as np
     ctx = {}
     n_tok = (n_tokens // 256) * 256
@@ -352,7 +352,7 @@ def context_numbers(lib, torch, dev, n_tokens, d, vc=8192):
     torch.cuda.synchronize()
     ms = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(5)]))
     tf = 2.0 * n_tok * vc * d / (ms * 1e-3) / 1e12
-    ctx["vendor_gemm"] = dict(what=f"torch.matmul bf16, [{vc} x {n_tok}] . [{n_tok} x {d}] (one d_w_lm launch's shape), "
+    ctx["vendor_gemm"] = dict(what=f"torch.matmul bf16, [{vc} x {n_tok}] . [{n_tok} x {d}] (d_w_lm's contraction for 8192 vocabulary columns), "
                                    "random normal operands, median of 5", ms=ms, tflops=tf, frac_of_peak=tf / PEAK_BF16_TFLOPS)
     del a, b, c, at
     sink = torch.zeros(1, dtype=torch.float32, device=dev)

@@ -852,7 +852,10 @@ __global__ __launch_bounds__(256) void transpose_kernel(LossHeader* __restrict__
                                                         const uint16_t* __restrict__ src, int64_t rows,
                                                         int d, int64_t rows_out, int token_rows,
                                                         uint16_t* __restrict__ dst) {
-    __shared__ uint16_t tile[64][66];
+    // 64 rows x 64 k per workgroup, 16 bytes per lane both ways: a lane reads 8 consecutive k of one row,
+    // scatters them into the transposed LDS tile, and later writes 8 consecutive rows of one k.
+    constexpr int kPitch = 72;                         // halfwords per k-row of the tile: 16-byte aligned rows
+    __shared__ __align__(16) uint16_t tile[64 * kPitch];
     int64_t nrows = rows, fill_to = rows_out;
     if (token_rows) {
         nrows = hdr->n_valid;
@@ -861,30 +864,42 @@ __global__ __launch_bounds__(256) void transpose_kernel(LossHeader* __restrict__
     const int64_t r0 = (int64_t)blockIdx.x * 64;
     const int k0 = blockIdx.y * 64;
     if (r0 >= fill_to) return;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int sub = threadIdx.x & 7, line = threadIdx.x >> 3;   // 8 granules of 8 x 32 lines per pass
     uint32_t amax = 0u;   // largest |x| seen, as bf16 bits (non-negative floats order as integers)
-    for (int rr = ty; rr < 64; rr += 4) {
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int rr = pass * 32 + line;
         const int64_t r = r0 + rr;
-        uint16_t x = 0;
-        if (r < nrows && k0 + tx < d) {
+        const int k = k0 + sub * 8;                    // d is a multiple of 8: a granule lies inside the row or outside
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (r < nrows && k < d) {
             const int64_t srow = gather ? (int64_t)gather[r] : r;
-            x = src[srow * d + k0 + tx];
+            raw = *reinterpret_cast<const u32x4*>(src + srow * d + k);
         }
-        tile[rr][tx] = x;
-        amax = max(amax, (uint32_t)(x & 0x7FFFu));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t lo = raw[j] & 0xFFFFu, hi = raw[j] >> 16;
+            tile[(sub * 8 + 2 * j) * kPitch + rr] = (uint16_t)lo;
+            tile[(sub * 8 + 2 * j + 1) * kPitch + rr] = (uint16_t)hi;
+            amax = max(amax, max(lo & 0x7FFFu, hi & 0x7FFFu));
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, off, 64));
-    if (tx == 0 && amax != 0u) {
+    if ((threadIdx.x & 63) == 0 && amax != 0u) {
         // a plain look first: after the first few workgroups nearly none still raises the maximum, and
         // hundreds of thousands of atomics on one address would take longer than the copy itself
         uint32_t* slot = token_rows ? &hdr->hmax_bits : &hdr->wmax_bits;
         if ((amax << 16) > *reinterpret_cast<volatile uint32_t*>(slot)) atomicMax(slot, amax << 16);
     }
     __syncthreads();
-    for (int kk = ty; kk < 64; kk += 4) {
-        const int64_t r = r0 + tx;
-        if (k0 + kk < d && r < rows_out) dst[((r / kTile) * d + (k0 + kk)) * kTile + r % kTile] = tile[tx][kk];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int kk = pass * 32 + line;
+        const int64_t r = r0 + sub * 8;                // 8 consecutive rows: inside one 256-row block of dst
+        if (k0 + kk < d && r < rows_out)
+            *reinterpret_cast<u32x4*>(dst + ((r / kTile) * d + (k0 + kk)) * kTile + r % kTile) =
+                *reinterpret_cast<const u32x4*>(&tile[kk * kPitch + sub * 8]);
     }
 }
 
