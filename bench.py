@@ -23,7 +23,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 / fp16 MFMA peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
 # Kernel names as rocprofv3 prints them, demangled or mangled, matched exactly (template arguments
-# included: the selector-stress launch is select_kernel<32, 8>, not the other group sizes' variants).
+# included: the selector-stress launch is select_quarter_kernel<64>, not the other group sizes' variants).
 KERNEL_SYMBOLS = {"token loss forward": (r"::fwd_kernel\(", r"\d+fwd_kernelE"),
                   "token loss normalise": (r"::rescale_kernel\(", r"\d+rescale_kernelE"),
                   "token loss d_hidden": (r"::dh_kernel\(", r"\d+dh_kernelE"),

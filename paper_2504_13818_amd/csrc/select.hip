@@ -688,15 +688,17 @@ __global__ __launch_bounds__(256, 2) void select_quarter_kernel(const float* __r
         int32_t* out = sel_idx + (size_t)group * kM + a;
 #pragma unroll
         for (int i = 0; i < kPer; i += 4) {
-            int4 w;
+            typedef int i32x4 __attribute__((ext_vector_type(4)));
+            i32x4 w;
             constexpr uint32_t kIdxMask = (1u << kIdxBits) - 1u;
-            w.x = (int)(((a + i + 0 < kM - best_k) ? lo_w[i + 0] : hi_w[i + 0]) & kIdxMask);
-            w.y = (int)(((a + i + 1 < kM - best_k) ? lo_w[i + 1] : hi_w[i + 1]) & kIdxMask);
-            w.z = (int)(((a + i + 2 < kM - best_k) ? lo_w[i + 2] : hi_w[i + 2]) & kIdxMask);
-            w.w = (int)(((a + i + 3 < kM - best_k) ? lo_w[i + 3] : hi_w[i + 3]) & kIdxMask);
-            *reinterpret_cast<int4*>(out + i) = w;
+            w[0] = (int)(((a + i + 0 < kM - best_k) ? lo_w[i + 0] : hi_w[i + 0]) & kIdxMask);
+            w[1] = (int)(((a + i + 1 < kM - best_k) ? lo_w[i + 1] : hi_w[i + 1]) & kIdxMask);
+            w[2] = (int)(((a + i + 2 < kM - best_k) ? lo_w[i + 2] : hi_w[i + 2]) & kIdxMask);
+            w[3] = (int)(((a + i + 3 < kM - best_k) ? lo_w[i + 3] : hi_w[i + 3]) & kIdxMask);
+            // written once, read by nobody here: streamed past the L2, so that no dirty lines wait for the kernel's end
+            __builtin_nontemporal_store(w, reinterpret_cast<i32x4*>(out + i));
         }
-        if (sel_k != nullptr && quad == 0) sel_k[group] = best_k;
+        if (sel_k != nullptr && quad == 0) __builtin_nontemporal_store(best_k, sel_k + group);
     }
 }
 
