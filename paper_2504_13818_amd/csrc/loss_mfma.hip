@@ -470,7 +470,8 @@ __device__ __forceinline__ void fwd_epilogue(const f32x16 (&acc)[4][4], const La
             const f16x4 lo = *reinterpret_cast<const f16x4*>(src);
             const f16x4 hi = *reinterpret_cast<const f16x4*>(src + 8);
             const f16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            *reinterpret_cast<f16x8*>(qtile + (int64_t)r * ldq + (g.lane & 31) * 8) = both;
+            // streamed past the L2, whose lines are better spent on the operand tiles the XCD's workgroups share
+            __builtin_nontemporal_store(both, reinterpret_cast<f16x8*>(qtile + (int64_t)r * ldq + (g.lane & 31) * 8));
         }
     }
     if (g.wm == 1 && g.lane < 32) {
