@@ -60,6 +60,18 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void advantage_kernel(
     for (int j = lane; j < m; j += kWave) a[j] = (float)(((double)r[s[j]] - mu) * inv);
 }
 
+// One word from src to dst, both streamed past the L2 (read once, written once: nothing here reads them again).
+template <typename W>
+__device__ __forceinline__ void copy_streaming(const W* s, W* d) {
+    if constexpr (sizeof(W) == 16) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(s)),
+                                    reinterpret_cast<u32x4*>(d));
+    } else {
+        __builtin_nontemporal_store(__builtin_nontemporal_load(s), d);
+    }
+}
+
 // Kept rollouts' records, concatenated over the prompts (Sec. 3.2).  blockIdx.x = output row
 // b*m + j, blockIdx.y = a slab of 1024 words of the row; W is the access word.
 template <typename W>
@@ -76,7 +88,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const W* __restrict__ 
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
         const size_t w = first + (size_t)i * 256;
-        if (w < row_words) d[w] = s[w];
+        if (w < row_words) copy_streaming(s + w, d + w);
     }
 }
 
