@@ -683,20 +683,48 @@ __global__ __launch_bounds__(256, 2) void select_quarter_kernel(const float* __r
     }
 
     PODS_PHASE_FENCE();
-    // ---- emit the (m-k) lowest then the k highest: output slot j = a + i
-    if (live) {
-        int32_t* out = sel_idx + (size_t)group * kM + a;
+    // ---- emit the (m-k) lowest then the k highest: output slot j = a + i.  The lane holds kPer consecutive slots
+    // as pieces of four; the pieces are transposed among the group's four lanes first (lane bit <-> piece bit, one
+    // swap per word), so that a store instruction writes 64 contiguous bytes per group instead of four 16-byte
+    // pieces 64 bytes apart: the stores go past the L2 (nontemporal: no dirty lines wait for the kernel's end),
+    // where nothing would merge such pieces into whole lines.
+    constexpr int kPieces = kPer / 4;
+    constexpr uint32_t kIdxMask = (1u << kIdxBits) - 1u;
+    uint32_t piece[kPieces][4];
 #pragma unroll
-        for (int i = 0; i < kPer; i += 4) {
-            typedef int i32x4 __attribute__((ext_vector_type(4)));
+    for (int i = 0; i < kPer; ++i)
+        piece[i / 4][i % 4] = ((a + i < kM - best_k) ? lo_w[i] : hi_w[i]) & kIdxMask;
+    if constexpr (kPieces >= 2) {      // lane bit 0 <-> piece bit 0
+#pragma unroll
+        for (int p = 0; p < kPieces; p += 2)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const auto r = __builtin_amdgcn_permlane16_swap(piece[p][c], piece[p + 1][c], false, false);
+                piece[p][c] = r[0];
+                piece[p + 1][c] = r[1];
+            }
+    }
+    if constexpr (kPieces >= 4) {      // lane bit 1 <-> piece bit 1
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const auto r = __builtin_amdgcn_permlane32_swap(piece[p][c], piece[p + 2][c], false, false);
+                piece[p][c] = r[0];
+                piece[p + 2][c] = r[1];
+            }
+    }
+    static_assert(kPieces == 1 || kPieces == 2 || kPieces == 4, "16, 32 or 64 keys per lane");
+    if (live) {
+        int32_t* out = sel_idx + (size_t)group * kM;
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int p = 0; p < kPieces; ++p) {
+            // piece p now holds: 4 pieces: lane quad p's piece `quad`; 2 pieces: lane (l1, p)'s piece l0; 1: its own
+            const int slot = kPieces == 4 ? 16 * p + 4 * quad : kPieces == 2 ? 8 * (2 * l1 + p) + 4 * l0 : 4 * quad;
             i32x4 w;
-            constexpr uint32_t kIdxMask = (1u << kIdxBits) - 1u;
-            w[0] = (int)(((a + i + 0 < kM - best_k) ? lo_w[i + 0] : hi_w[i + 0]) & kIdxMask);
-            w[1] = (int)(((a + i + 1 < kM - best_k) ? lo_w[i + 1] : hi_w[i + 1]) & kIdxMask);
-            w[2] = (int)(((a + i + 2 < kM - best_k) ? lo_w[i + 2] : hi_w[i + 2]) & kIdxMask);
-            w[3] = (int)(((a + i + 3 < kM - best_k) ? lo_w[i + 3] : hi_w[i + 3]) & kIdxMask);
-            // written once, read by nobody here: streamed past the L2, so that no dirty lines wait for the kernel's end
-            __builtin_nontemporal_store(w, reinterpret_cast<i32x4*>(out + i));
+            w[0] = (int)piece[p][0]; w[1] = (int)piece[p][1]; w[2] = (int)piece[p][2]; w[3] = (int)piece[p][3];
+            __builtin_nontemporal_store(w, reinterpret_cast<i32x4*>(out + slot));
         }
         if (sel_k != nullptr && quad == 0) __builtin_nontemporal_store(best_k, sel_k + group);
     }
