@@ -233,7 +233,8 @@ def make_inputs(torch, inputs, cfg, dev):
 GEMM_NAMES = ["token loss forward", "token loss d_hidden", "token loss d_w_lm"]
 
 
-def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False, with_skip=False):
+def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False, with_skip=False,
+               with_constant_operands=False):
     """Times `steps` whole steps (pods_select + pods_advantage + grpo_token_loss_fwd_bwd) of one config, with
     HIP events around every kernel launch."""
     import numpy as np
@@ -328,6 +329,26 @@ def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False,
         res["skip_zero_advantage"] = dict(
             ms_per_step=skip_ms, steps=skip_steps, valid_tokens=n_valid, tokens_back_propagated=live,
             note="not the headline: value counts every valid token and is measured without skipping")
+    if with_constant_operands:
+        # Context for the roofline fraction (never a result): the very same launches on hidden states that are all
+        # zero, so that every logit is 0, all softmax numerators are equal and one operand of every matrix
+        # instruction is constant.  The instruction streams, addresses and bytes moved are those of the headline
+        # step; what changes is how many operand bits toggle, i.e. the power the matrix pipe draws.
+        x["hidden"].zero_()
+        const_steps = max(3, steps // 4)
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(const_steps):
+            step()
+        torch.cuda.synchronize()
+        const_ms = (time.perf_counter() - t0) * 1e3 / const_steps
+        res["constant_operands"] = dict(
+            what="the headline step's launches on all-zero hidden states (equal softmax numerators, one constant "
+                 "operand per matrix instruction): same instructions, addresses and traffic, fewer toggling bits",
+            ms_per_step=const_ms, steps=const_steps,
+            tflops=3 * flops_family / (const_ms * 1e-3) / 1e12,
+            frac_of_peak=3 * flops_family / (const_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS)
     return res
 
 
@@ -402,7 +423,7 @@ def main():
     torch.cuda.set_device(dev)
     cfg = args.config
     head = run_config(lib, torch, inputs, cfg, args.steps, args.warmup, dev, traffic_probe=args.traffic_probe,
-                      with_skip=True)
+                      with_skip=True, with_constant_operands=not args.only_headline)
     torch.cuda.empty_cache()
     c = inputs.CONFIGS[cfg]
 
@@ -442,6 +463,7 @@ def main():
         result["configs"] = others
         result["gather"] = time_gather(lib, torch, args.steps)
         result["context"] = context_numbers(lib, torch, dev, head["n_valid"], c["d"])
+        result["context"]["constant_operands"] = head["constant_operands"]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_loss(inputs, cfg)
         result["selector"]["cpu_baseline"] = cpu_selector(inputs)
