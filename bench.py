@@ -121,6 +121,23 @@ def current_logp_torch(torch, hidden, w, tokens, chunk=4096):
     return out.reshape(R, T)
 
 
+def sample_tokens_torch(torch, hidden, w, generator, chunk=4096):
+    """Tokens drawn from softmax(hidden . w^T) (Gumbel-max) and their log-probs, with plain torch ops in token
+    chunks (input synthesis only, for the context measurement on policy-sampled tokens)."""
+    R, T, d = hidden.shape
+    h2 = hidden.reshape(R * T, d)
+    tok = torch.empty(R * T, dtype=torch.int64, device=hidden.device)
+    logp = torch.empty(R * T, dtype=torch.float32, device=hidden.device)
+    for s in range(0, R * T, chunk):
+        z = (h2[s:s + chunk] @ w.T).float()
+        u = torch.rand(z.shape, generator=generator, device=z.device).clamp_(1e-20, 1.0)
+        t = (z - torch.log(-torch.log(u))).argmax(dim=1)
+        tok[s:s + chunk] = t
+        logp[s:s + chunk] = z.gather(1, t[:, None])[:, 0] - torch.logsumexp(z, dim=1)
+        del z, u
+    return tok.reshape(R, T).to(torch.int32), logp.reshape(R, T)
+
+
 def time_selector(lib, torch, inputs, steps):
     """pods_select on the selector-stress workload (B=65536, n=256, m=64), rotating over enough
     buffer sets that no input or output is served from the 256 MiB Infinity Cache."""
@@ -330,6 +347,38 @@ def run_config(lib, torch, inputs, cfg, steps, warmup, dev, traffic_probe=False,
             ms_per_step=skip_ms, steps=skip_steps, valid_tokens=n_valid, tokens_back_propagated=live,
             note="not the headline: value counts every valid token and is measured without skipping")
     if with_constant_operands:
+        # Context (never a result): the same shapes with a softmax as peaked as a trained policy's and tokens that
+        # were sampled from it, instead of the workload's flat softmax (logit standard deviation 0.9, entropy
+        # 11.5 nats) and uniformly drawn tokens.  Hidden states times 5: logit standard deviation 4.5.
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(inputs.seed_for(cfg, 6))
+        x["hidden"].mul_(5.0)
+        toks, cur = sample_tokens_torch(torch, x["hidden"], x["w"], gen)
+        x["tokens"].copy_(toks)
+        x["old_logp"].copy_(cur + 0.05 * torch.randn(cur.shape, generator=gen, device=dev))
+        valid = torch.arange(T, device=dev)[None, :] < x["lengths"][:, None]
+        mean_logp = float(cur[valid].mean().cpu())
+        del toks, cur
+        peak_steps = max(3, steps // 4)
+        step()
+        torch.cuda.synchronize()
+        lib.pods_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(peak_steps):
+            step()
+        torch.cuda.synchronize()
+        peak_ms = (time.perf_counter() - t0) * 1e3 / peak_steps
+        pk = {}
+        for name, ms in lib.pods_profile_read():
+            pk[name] = pk.get(name, 0.0) + ms / peak_steps
+        lib.pods_profile_enable(False)
+        res["policy_sampled_peaked"] = dict(
+            what="the headline shapes with hidden states times 5 (logit standard deviation 4.5) and tokens sampled from "
+                 "the policy itself (Gumbel-max), old_logp = their log-prob + N(0, 0.05)",
+            mean_logp_of_sampled_tokens=mean_logp, ms_per_step=peak_ms, steps=peak_steps,
+            tokens_per_s=n_valid / (peak_ms * 1e-3),
+            frac_of_peak=3 * flops_family / (peak_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            kernel_ms_per_step={k: pk[k] for k in GEMM_NAMES + ["token loss normalise"] if k in pk})
         # Context for the roofline fraction (never a result): the very same launches on hidden states that are all
         # zero, so that every logit is 0, all softmax numerators are equal and one operand of every matrix
         # instruction is constant.  The instruction streams, addresses and bytes moved are those of the headline
@@ -464,6 +513,7 @@ def main():
         result["gather"] = time_gather(lib, torch, args.steps)
         result["context"] = context_numbers(lib, torch, dev, head["n_valid"], c["d"])
         result["context"]["constant_operands"] = head["constant_operands"]
+        result["context"]["policy_sampled_peaked"] = head["policy_sampled_peaked"]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_loss(inputs, cfg)
         result["selector"]["cpu_baseline"] = cpu_selector(inputs)

@@ -180,8 +180,8 @@ __global__ __launch_bounds__(256) void zero_pad_rows_kernel(const int32_t* __res
 // BASE2 = false (plain path): a partial is (m, sum exp(z - m)).
 // BASE2 = true (matrix-core path): a partial is (E, sum exp(z) 2^-E) with E an integer, so partials combine
 // by exact powers of two; besides lse the kernel writes, for the softmax numerators 2^14 exp(z) 2^-E kept by
-// the forward pass: Eref = the largest E among the token's tiles, cscale[p] = 2^Eref exp(-lse) (at most 8, at
-// least 1/V: the largest logit lies within 3 binades below 2^Eref), and qscale[tile][p] = 2^(E - Eref) <= 1
+// the forward pass: Eref = the largest E among the token's tiles, cscale[p] = 2^Eref exp(-lse) (below 32, at
+// least 1/V: the largest logit lies within 5 binades below 2^Eref), and qscale[tile][p] = 2^(E - Eref) <= 1
 // in fp16 (exact; 0 below 2^-24), so that 2^14 softmax = numerator * qscale * cscale.  Every tile that
 // already used Eref, which after the first forward launch of a token block is the rule, has qscale = 1.
 constexpr int kLseWaves = 16;

@@ -19,7 +19,7 @@
 // from the forward pass, under a power-of-two offset per (token, vocabulary tile), spares the backward pass a
 // second logits contraction (2 N d V of the 8 N d V floating-point operations a recomputing backward pass
 // executes).  After a block's first forward launch (the first 8192 vocabulary columns) every token fixes the
-// exponent its later tiles use: two above the larger of the first launch's exponents and that of the generated
+// exponent its later tiles use: four above the larger of the first launch's exponents and that of the generated
 // token's own logit, which a policy that sampled the token has made large.  A tile takes the agreed exponent
 // unless its own lies two or more above it, so for nearly every token all later tiles share one offset and the
 // normalising pass has only the first launch's tiles (and such rare tokens) to touch; the remaining per-token
@@ -528,11 +528,13 @@ __global__ __launch_bounds__(256, 1) void fwd_kernel(const LossHeader* __restric
 }
 
 // ------------------------------------------------------------------------------------------
-// The exponent a token's vocabulary tiles agree on, fixed after the block's first forward launch: two above the
+// The exponent a token's vocabulary tiles agree on, fixed after the block's first forward launch: four above the
 // larger of (a) the exponents of that launch's `slots0` tiles and (b) that of the generated token's own logit
 // z_y = h_t . W_y (fp32 dot product of the bf16 rows; only its binade matters here).  One wave per token.
 // ------------------------------------------------------------------------------------------
-constexpr float kExponentMargin = 2.0f;
+// (The margin costs nothing in precision: the largest numerator of a token keeps all its bits, and fp16 still holds
+// full precision 24 binades below 2^14 2^-margin, i.e. down to softmax terms e^-16 of the largest.)
+constexpr float kExponentMargin = 4.0f;
 __global__ __launch_bounds__(256) void exponent_kernel(const LossHeader* __restrict__ hdr,
                                                        const int32_t* __restrict__ row_map,
                                                        const int32_t* __restrict__ tok,
