@@ -71,7 +71,7 @@ def test_loss_argument_checks_and_workspace_query():
                                    (16, 64, 256, 1024), (1, 1, 64, 40000)])
 def test_workspace_layout_never_exceeds_the_workspace(shape):
     """For every workspace size from the minimum to beyond the recommendation, the arrays a call lays out
-    end inside the workspace (the layout's size is not monotone in the vocabulary chunk it picks)."""
+    end inside the workspace (the token block a size allows is found by search, and every array is laid out from it)."""
     R, T, d, V = shape
     least = lib.grpo_token_loss_workspace_min_bytes(R, T, d, V, lib.PODS_BF16)
     rec = lib.grpo_token_loss_workspace_bytes(R, T, d, V, lib.PODS_BF16)

@@ -42,7 +42,7 @@ def test_bf16_small_shapes(pods, R, T, d, V):
     H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale))
 
 
-def test_bf16_small_workspace_many_chunks(pods):
+def test_bf16_small_workspace_many_token_blocks(pods):
     case = H.loss_case(4, 4, 128, 256, 3000, sigma=0.2)
     ws = torch.empty((pods.grpo_token_loss_workspace_min_bytes(4, 128, 256, 3000, pods.PODS_BF16),),
                      dtype=torch.uint8, device="cuda")

@@ -41,7 +41,7 @@ def _sweep(lib, lo, hi, step, n1_hi):
 
 
 def test_every_grid_up_to_the_token_tiles_of_the_benchmark_shapes(harness):
-    """Token tiles (n0) up to 2100 x second axis up to 40: covers the forward / recompute launches (up to 32
+    """Token tiles (n0) up to 2100 x second axis up to 40: covers the forward launches (up to 32
     vocabulary tiles per launch at the default chunk) and d_hidden (up to 16 d-tiles at d = 4096), on
     both sides of the few-blocks switch."""
     _sweep(harness, 1, 2100, 1, 40)     # includes 576, 1152, 2048: the capacities R*T/256 of the benchmark shapes

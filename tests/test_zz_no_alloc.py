@@ -52,7 +52,7 @@ def test_static_workspace_entry_matches_the_workspace_entry(pods):
         assert got["loss"] == same["loss"]
         for key in ("logp", "d_hidden", "d_w"):
             assert np.array_equal(got[key], same[key]), key
-        # ... and on its recommended workspace, within the parity bar (another vocabulary chunk, another
+        # ... and on its recommended workspace, within the parity bar (another token block size, another
         # summation order), as is the oracle
         rec = H.gpu_loss(pods, torch, case, grad_scale=scale)
         H.check_loss(got, rec)
