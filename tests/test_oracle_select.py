@@ -1,7 +1,9 @@
 """Pins for the selector oracle (Alg. 2, Lemma 3.1, Theorems 1 and 2).  CPU only."""
 import itertools
-from fractions import Fraction
+import multiprocessing as mp
 import os
+from fractions import Fraction
+
 import numpy as np
 import pytest
 
@@ -171,8 +173,6 @@ def test_c_oracle_equals_exact_rule_on_a_slice_of_the_stress_config():
     """The batched C oracle is the reference the GPU selector is compared with on all 65536 groups of the
     selector-stress config; here it is itself held to the paper's rule in exact rational arithmetic on the
     config's first 2048 groups (n = 256, m = 64; continuous rewards, about a tenth of the groups constant)."""
-    import multiprocessing as mp
-    from paper_2504_13818_amd import inputs
     r = inputs.rewards(3, B=2048)
     idx, k, _ = fast.select(r, 64)
     workers = min(8, os.cpu_count() or 1)
