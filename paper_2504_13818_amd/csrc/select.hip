@@ -445,9 +445,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ r
 // Direction: every compare-exchange is ascending in the value as stored.  A run that must descend for
 // the next merge is sorted ascending on negated keys and then has its sign flipped (one XOR per key):
 // these keys are doubles in [2, 4), never zero, so negation reverses their order exactly.
-// After the first two stages of the last merge the lowest and the highest quarter are separated from
-// the middle half, which Theorem 1 never reads: the registers of the middle half are dropped, and the
-// remaining stages run on half the keys.
+// The last merge starts with one half-cleaner across the two runs' lower halves and one across their upper
+// halves, which separates the lowest and the highest quarter from the middle half; Theorem 1 never reads the
+// middle half, so its registers are dropped, and the remaining stages run on half the keys.
 // The last transpositions leave lane L = 0..3 of the group with sorted positions [L n/16, (L+1) n/16) of
 // the lowest quarter and the same offsets of the highest quarter in registers, which is exactly the
 // block of candidate splits k a lane scores (split k drops the low position m-k and adds the high
@@ -589,8 +589,17 @@ __global__ __launch_bounds__(256, 2) void select_quarter_kernel(const float* __r
     // ---- merge of the two runs of 2 KPL (lanes 32 apart) into the sorted group, outer quarters only
     flip_sign<KPL>(key, l1 ? 0x80000000u : 0u);                  // the upper run now descends (all keys true)
     transpose_bit<KPL, 1, 1>(key, all);                          // lane bit 1 <- e0, register bit 1 <- e(kR+1)
-    stage_reg_bit<KPL, 1>(key, all);                             // stride 2 KPL
-    stage_reg_bit<KPL, 0>(key, all);                             // stride KPL
+    // Registers with bits (1, 0) = 00, 01 now hold the lower and the upper half of the ascending run, 10 and 11 the
+    // upper and the lower half of the descending one.  Theorem 1 reads the m lowest and the m highest of the group
+    // only: the m lowest lie in the two lower halves, and one half-cleaner across them (ascending half against
+    // descending half, element by element) leaves exactly them, as a bitonic sequence, in its minima; likewise the
+    // m highest in the maxima across the two upper halves.  (The full merge would spend two stages, three times as
+    // many instructions, to get the same two quarters.)
+#pragma unroll
+    for (int r = 0; r < KPL; r += 4) {
+        key[r] = fmin(key[r], key[r | 3]);                       // the lowest quarter
+        key[r | 3] = fmax(key[r | 1], key[r | 2]);               // the highest quarter
+    }
     // registers with bits (1, 0) = 00 hold the lowest quarter, 11 the highest; 01 and 10 are never read again
     auto outer = [](int r) { return (r & 3) == 0 || (r & 3) == 3; };
     stages_reg_bits<KPL, kR - 1, 2>(key, outer);                 // strides KPL/2 .. 4
