@@ -646,10 +646,6 @@ __global__ __launch_bounds__(256, 2) void select_quarter_kernel(const float* __r
         bh1 += x;
         bh2 += x * x;
     }
-    // The candidate walk below converts the rewards to double again: without this the compiler keeps the 32
-    // doubles and their 32 squares of the block sums alive across the scans (128 registers).
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) asm volatile("" : "+v"(lo_r[i]), "+v"(hi_r[i]));
     PODS_PHASE_FENCE();
     // sums of the low range below this lane's block, of the high range above it
     const double tl1 = partner<16>(bl1, lane), tl2 = partner<16>(bl2, lane);
