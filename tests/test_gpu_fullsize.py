@@ -1,5 +1,5 @@
 """GPU parity at the benchmark's full sizes (configs 1, 2 and 4: the Qwen2.5-3B-, Qwen2.5-7B- and
-Llama-3.2-3B-shaped heads, bf16), in the launch configuration bench.py times.
+Llama-3-8B-shaped heads, bf16), in the launch configuration bench.py times.
 
 The oracle cannot finish this size, so: selection and advantages are compared in full (they are
 small); log-probs and d_hidden are compared on sampled tokens, which the oracle computes one by
