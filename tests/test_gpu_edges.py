@@ -40,6 +40,18 @@ def test_bf16_tiny_and_tile_boundaries(pods, R, T, d, V):
     H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale, gemm_dtype=np.float64))
 
 
+@pytest.mark.parametrize("V", [65000, 65300, 70001])
+def test_bf16_vocabulary_at_the_switch_of_the_d_w_lm_tile_order(pods, V):
+    """d_w_lm walks its tiles in strips, one round of the chip per launch, from 256 vocabulary tiles on (V above
+    65280); below, in the general order with one launch.  One size below the switch, one just above (256 tiles, the
+    last one ragged), one with a partly filled last strip; a single d-tile, so that a round takes 64 strips."""
+    R, T, d = 3, 200, 64
+    case = H.loss_case(1, R, T, d, V, sigma=0.2)
+    H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case))
+    scale = float(R * case["lengths"].mean())
+    H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale))
+
+
 def test_more_rollouts_than_one_grid_dimension(pods):
     """R above 65535 (many short rollouts): nothing in the path may ride on a 16-bit grid dimension."""
     R, T, d, V = 66000, 3, 64, 300
