@@ -230,7 +230,9 @@ size_t grpo_token_loss_workspace_used_bytes(int32_t R, int32_t T, int32_t d, int
  * copied to fp16 under power-of-two scales taken from their largest magnitudes (exact for elements
  * within 2^22 of the largest, see pods_loss_report), and the generated token's own logit is applied
  * in fp32; results are deterministic (no floating-point atomics).  A bf16 call with d not a multiple
- * of 64, and every fp32 call, uses plain fp32 vector arithmetic throughout.  d <= 16384, R*T <= 2^30,
+ * of 8, and every fp32 call, uses plain fp32 vector arithmetic throughout (orders of magnitude slower); bf16
+ * with d a multiple of 8 runs on the matrix cores, the working copies padded with zeros to a multiple of 64
+ * (hidden and w_lm must be 16-byte aligned).  d <= 16384, R*T <= 2^30,
  * T <= 16776960 (PODS_ERR_UNSUPPORTED beyond).
  */
 pods_status grpo_token_loss_fwd_bwd(const void* hidden, const void* w_lm, const int32_t* tokens,

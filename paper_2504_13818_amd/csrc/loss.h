@@ -93,7 +93,7 @@ constexpr int kDefaultTokenBlock = 32768;   // packed token rows whose softmax n
 struct LossPlan {
     int64_t ncap;     // R*T
     int64_t ncap_ld;  // ncap rounded up to kTile: rows of the per-token arrays
-    bool mfma;        // bf16 inputs with d % 64 == 0 take the matrix-core path
+    bool mfma;        // bf16 inputs with d % 8 == 0 take the matrix-core path
     int slots;        // forward partial slots per token (one per vocabulary tile on the matrix-core path)
     int64_t nb;       // matrix-core path: packed token rows per block (multiple of kTile); the block's softmax
                       // numerators q[nb][ldq] are the only [tokens, vocabulary]-shaped array that ever exists
@@ -101,6 +101,7 @@ struct LossPlan {
     int64_t ldq;      // row pitch of q in elements: the padded vocabulary plus one tile, so rows do not sit a
                       // power of two apart
     int64_t vld;      // V rounded up to kTile: rows of the fp16 weight copy, columns of the transposed one
+    int dk;           // d rounded up to 64: the contraction length of the working copies (zero beyond d)
     int loss_blocks;
     size_t off_hdr, off_gmax, off_offsets, off_rowmap, off_tok, off_lse, off_zy, off_g, off_coef, off_cscale, off_efix, off_pmax,
         off_psum, off_qscale, off_losspart, off_wtt, off_htt, off_wt, off_ht, off_dz, total;

@@ -9,7 +9,9 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     LossPlan p{};
     p.ncap = (int64_t)R * T;
     p.ncap_ld = (p.ncap + kTile - 1) / kTile * kTile;
-    p.mfma = (dt == PODS_BF16) && (d % 64 == 0);
+    // the matrix-core path reads 16-byte granules of the bf16 rows; its working copies pad d to a multiple of 64
+    p.mfma = (dt == PODS_BF16) && (d % 8 == 0);
+    p.dk = (d + 63) / 64 * 64;
     p.slots = p.mfma ? (int)(((int64_t)V + kTile - 1) / kTile) : 1;   // one partial per vocabulary tile
     p.loss_blocks = (int)ceil_div(p.ncap, 256);
     size_t off = 0;
@@ -45,10 +47,10 @@ LossPlan plan_loss(int32_t R, int32_t T, int32_t d, int32_t V, pods_dtype dt, si
     const int64_t vround = ((int64_t)V + kTile - 1) / kTile * kTile;
     p.vld = vround;
     p.ldq = vround + kTile;
-    p.off_wtt = take(2 * (size_t)d * (size_t)vround);        // transposed bf16 weight, [vround/256][d][256]
-    p.off_htt = take(2 * (size_t)d * (size_t)p.ncap_ld);     // transposed bf16 hidden, [ncap_ld/256][d][256]
-    p.off_wt = take(2 * (size_t)d * (size_t)vround);         // fp16 weight copy (zero rows past V)
-    p.off_ht = take(2 * (size_t)d * (size_t)p.ncap_ld);      // fp16 packed, g-scaled hidden
+    p.off_wtt = take(2 * (size_t)p.dk * (size_t)vround);     // transposed bf16 weight, [vround/256][dk][256]
+    p.off_htt = take(2 * (size_t)p.dk * (size_t)p.ncap_ld);  // transposed bf16 hidden, [ncap_ld/256][dk][256]
+    p.off_wt = take(2 * (size_t)p.dk * (size_t)vround);      // fp16 weight copy [vround][dk] (zero rows past V)
+    p.off_ht = take(2 * (size_t)p.dk * (size_t)p.ncap_ld);   // fp16 packed, g-scaled hidden [ncap_ld][dk]
     p.off_dz = off;                                          // q[nb][ldq] fp16, the last array
     const size_t row_bytes = 2 * (size_t)p.ldq;
     const int64_t rec_nb = p.ncap_ld < kDefaultTokenBlock ? p.ncap_ld : kDefaultTokenBlock;

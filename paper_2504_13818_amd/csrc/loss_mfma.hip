@@ -617,7 +617,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
                                                     const float* __restrict__ gvec,
                                                     const uint16_t* __restrict__ w16,
                                                     const uint16_t* __restrict__ q, int64_t ldq, int d,
-                                                    int V, int64_t row0, int ntt_grid,
+                                                    int dk, int V, int64_t row0, int ntt_grid,
                                                     float* __restrict__ d_hidden) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int64_t n_valid = hdr->n_bwd;
@@ -628,7 +628,7 @@ __global__ __launch_bounds__(256, 1) void dh_kernel(const LossHeader* __restrict
     const LaneGeom g = lane_geom();
 
     Operand A, B;
-    operand_kmajor(A, w16, d, 0, kt0 * kTile, d);    // rows v >= V of W16 are zero
+    operand_kmajor(A, w16, dk, 0, kt0 * kTile, dk);  // rows v >= V and columns k >= d of W16 are zero
     // every row of a token tile that holds a valid row was written by the forward step (zeros past N)
     operand_rows(B, q, ldq, tb * kTile, (tb + 1) * kTile, 0);
     f32x16 acc[4][4];
@@ -711,8 +711,9 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
                                                     const uint32_t* __restrict__ gmax_block,
                                                     const uint16_t* __restrict__ h16,
                                                     const uint16_t* __restrict__ q, int64_t ldq,
-                                                    int d, int V, int64_t row0, int64_t nb, int first_block,
-                                                    int accumulate, int64_t wg0, float* __restrict__ d_w) {
+                                                    int d, int dk, int V, int64_t row0, int64_t nb,
+                                                    int first_block, int accumulate, int64_t wg0,
+                                                    float* __restrict__ d_w) {
     extern __shared__ __align__(16) unsigned char lds[];
     int64_t n_rows = hdr->n_bwd - row0;               // rows of this block that take part
     n_rows = n_rows < 0 ? 0 : (n_rows > nb ? nb : n_rows);
@@ -727,7 +728,7 @@ __global__ __launch_bounds__(256, 1) void dw_kernel(const LossHeader* __restrict
 
     Operand A, B;
     // token rows past N (up to the end of the last token tile) are zero in H16 and finite in q
-    operand_kmajor(A, h16, d, row0, kt0 * kTile, d);
+    operand_kmajor(A, h16, dk, row0, kt0 * kTile, dk);
     operand_kmajor(B, q, ldq, 0, vt * kTile, vround);
     f32x16 acc[4][4];
     zero_acc(acc);
@@ -772,7 +773,7 @@ __global__ __launch_bounds__(256) void dh_onehot_kernel(const LossHeader* __rest
     const float c = coef[p];
     const uint16_t* wrow = w + (int64_t)tok[p] * d;
     float* out = d_hidden + (int64_t)row_map[p] * d;
-    for (int k = lane * 8; k < d; k += 512) {   // d % 64 == 0: whole groups of 8
+    for (int k = lane * 8; k < d; k += 512) {   // d % 8 == 0: whole groups of 8
         const u32x4 raw = *reinterpret_cast<const u32x4*>(wrow + k);
         f32x4 lo, hi;
 #pragma unroll
@@ -853,7 +854,7 @@ __global__ __launch_bounds__(256) void dw_onehot_kernel(const LossHeader* __rest
 __global__ __launch_bounds__(256) void transpose_kernel(LossHeader* __restrict__ hdr,
                                                         const int32_t* __restrict__ gather,
                                                         const uint16_t* __restrict__ src, int64_t rows,
-                                                        int d, int64_t rows_out, int token_rows,
+                                                        int d, int dk, int64_t rows_out, int token_rows,
                                                         uint16_t* __restrict__ dst) {
     // 64 rows x 64 k per workgroup, 16 bytes per lane both ways: a lane reads 8 consecutive k of one row,
     // scatters them into the transposed LDS tile, and later writes 8 consecutive rows of one k.
@@ -900,8 +901,8 @@ __global__ __launch_bounds__(256) void transpose_kernel(LossHeader* __restrict__
     for (int pass = 0; pass < 2; ++pass) {
         const int kk = pass * 32 + line;
         const int64_t r = r0 + sub * 8;                // 8 consecutive rows: inside one 256-row block of dst
-        if (k0 + kk < d && r < rows_out)
-            *reinterpret_cast<u32x4*>(dst + ((r / kTile) * d + (k0 + kk)) * kTile + r % kTile) =
+        if (k0 + kk < dk && r < rows_out)              // k in [d, dk): zeros
+            *reinterpret_cast<u32x4*>(dst + ((r / kTile) * dk + (k0 + kk)) * kTile + r % kTile) =
                 *reinterpret_cast<const u32x4*>(&tile[kk * kPitch + sub * 8]);
     }
 }
@@ -920,8 +921,8 @@ __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restri
                                                       const int32_t* __restrict__ gather,
                                                       const float* __restrict__ gvec,
                                                       const uint16_t* __restrict__ src, int64_t row0,
-                                                      int64_t rows, int64_t rows_valid, int d, int token_rows,
-                                                      _Float16* __restrict__ dst) {
+                                                      int64_t rows, int64_t rows_valid, int d, int dk,
+                                                      int token_rows, _Float16* __restrict__ dst) {
     int64_t nrows = rows_valid, fill_to = row0 + rows;
     float common;
     if (token_rows) {
@@ -932,7 +933,7 @@ __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restri
     } else {
         common = w_range_scale(hdr);
     }
-    const int per_row = d / 8;
+    const int per_row = dk / 8;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t r = row0 + idx / per_row;
     const int k = (int)(idx % per_row) * 8;
@@ -940,7 +941,7 @@ __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restri
     f16x8 out;
 #pragma unroll
     for (int j = 0; j < 8; ++j) out[j] = (_Float16)0.0f;
-    if (r < nrows) {
+    if (r < nrows && k < d) {   // d is a multiple of 8: a granule lies inside the row or in the zero padding
         const int64_t srow = gather ? (int64_t)gather[r] : r;
         const u32x4 raw = *reinterpret_cast<const u32x4*>(src + srow * d + k);
         const float sc = token_rows ? common * gvec[r] : common;
@@ -950,7 +951,7 @@ __global__ __launch_bounds__(256) void convert_kernel(const LossHeader* __restri
             out[2 * j + 1] = (_Float16)(__uint_as_float(raw[j] & 0xFFFF0000u) * sc);
         }
     }
-    *reinterpret_cast<f16x8*>(dst + r * d + k) = out;
+    *reinterpret_cast<f16x8*>(dst + r * dk + k) = out;
 }
 
 pods_status reserve(const void* kernel, const char* what, int bytes = kLdsBytes) {
@@ -988,16 +989,16 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
     if ((st = reserve(reinterpret_cast<const void*>(dw_kernel), "token loss d_w_lm")) != PODS_OK) return st;
 
     // once per call: transposed bf16 copies for the logits (they also find max |W|, max |h|), fp16 copy of W
-    const unsigned dtiles64 = (unsigned)ceil_div(a.d, 64);
+    const unsigned dtiles64 = (unsigned)(p.dk / 64);
     PODS_LAUNCH("transpose W", a.stream, transpose_kernel, dim3((unsigned)(p.vld / 64), dtiles64), dim3(256), 0,
-                a.stream, hdr, nullptr, w, (int64_t)a.V, a.d, p.vld, 0, wt);
+                a.stream, hdr, nullptr, w, (int64_t)a.V, a.d, p.dk, p.vld, 0, wt);
     if ((st = check_launch("transpose W")) != PODS_OK) return st;
     PODS_LAUNCH("transpose H", a.stream, transpose_kernel, dim3((unsigned)(p.ncap_ld / 64), dtiles64), dim3(256), 0,
-                a.stream, hdr, row_map, hidden, (int64_t)0, a.d, p.ncap_ld, 1, ht);
+                a.stream, hdr, row_map, hidden, (int64_t)0, a.d, p.dk, p.ncap_ld, 1, ht);
     if ((st = check_launch("transpose H")) != PODS_OK) return st;
-    const int64_t per_row = a.d / 8;
+    const int64_t per_row = p.dk / 8;
     PODS_LAUNCH("convert W", a.stream, convert_kernel, dim3((unsigned)ceil_div(p.vld * per_row, 256)), dim3(256), 0,
-                a.stream, hdr, nullptr, nullptr, nullptr, w, (int64_t)0, p.vld, (int64_t)a.V, a.d, 0, w16);
+                a.stream, hdr, nullptr, nullptr, nullptr, w, (int64_t)0, p.vld, (int64_t)a.V, a.d, p.dk, 0, w16);
     if ((st = check_launch("convert W")) != PODS_OK) return st;
 
     const int64_t nvt = p.vld / kTile;
@@ -1013,7 +1014,7 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
             const int64_t nl = nvt - vt0 < step_vt ? nvt - vt0 : step_vt;
             PODS_LAUNCH("token loss forward", a.stream, fwd_kernel, dim3((unsigned)super_grid_blocks(ntt, nl)),
                         dim3(256), kFwdLdsBytes, a.stream, hdr, tok, reinterpret_cast<const uint16_t*>(ht),
-                        reinterpret_cast<const uint16_t*>(wt), a.d, a.V, (int)vt0, (int)nl, row0, (int)ntt,
+                        reinterpret_cast<const uint16_t*>(wt), p.dk, a.V, (int)vt0, (int)nl, row0, (int)ntt,
                         p.ncap_ld, vt0 == 0 ? static_cast<const float*>(nullptr) : efix, pmax, psum, zy, p.ldq, q);
             if ((st = check_launch("token loss forward")) != PODS_OK) return st;
             if (vt0 == 0 && nl < nvt) {   // later launches write under the exponent each token fixes now
@@ -1029,14 +1030,14 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
                     qscale, p.ncap_ld, row0, (int)nvt, p.ldq, q);
         if ((st = check_launch("token loss normalise")) != PODS_OK) return st;
         PODS_LAUNCH("convert H", a.stream, convert_kernel, dim3((unsigned)ceil_div(rows * per_row, 256)), dim3(256), 0,
-                    a.stream, hdr, gmax + b, row_map, g, hidden, row0, rows, (int64_t)0, a.d, 1, h16);
+                    a.stream, hdr, gmax + b, row_map, g, hidden, row0, rows, (int64_t)0, a.d, p.dk, 1, h16);
         if ((st = check_launch("convert H")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_hidden (y logit)", a.stream, dh_onehot_kernel, dim3((unsigned)ceil_div(rows, 4)),
                     dim3(256), 0, a.stream, hdr, row_map, tok, coef, w, a.d, row0, a.d_hidden);
         if ((st = check_launch("token loss d_hidden (y logit)")) != PODS_OK) return st;
         PODS_LAUNCH("token loss d_hidden", a.stream, dh_kernel, dim3((unsigned)super_grid_blocks(ntt, dt256)), dim3(256),
                     kDhLdsBytes, a.stream, hdr, row_map, g, reinterpret_cast<const uint16_t*>(w16),
-                    reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, (int)ntt, a.d_hidden);
+                    reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, p.dk, a.V, row0, (int)ntt, a.d_hidden);
         if ((st = check_launch("token loss d_hidden")) != PODS_OK) return st;
         // With many vocabulary tiles: one launch per round of the chip (see decode_strip_tile).
         const bool strips = use_strips(nvt);
@@ -1046,7 +1047,7 @@ pods_status mfma_forward_backward(const LossArgs& a, const LossPlan& p) {
             const int64_t nwg = dw_total - wg0 < dw_round ? dw_total - wg0 : dw_round;
             PODS_LAUNCH("token loss d_w_lm", a.stream, dw_kernel, dim3((unsigned)nwg), dim3(256),
                         kLdsBytes, a.stream, hdr, gmax + b, reinterpret_cast<const uint16_t*>(h16),
-                        reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, a.V, row0, rows, b == 0 ? 1 : 0,
+                        reinterpret_cast<const uint16_t*>(q), p.ldq, a.d, p.dk, a.V, row0, rows, b == 0 ? 1 : 0,
                         (a.accumulate_d_w || b > 0) ? 1 : 0, wg0, a.d_w_lm);
         }
         if ((st = check_launch("token loss d_w_lm")) != PODS_OK) return st;

@@ -67,8 +67,29 @@ def test_more_rollouts_than_one_grid_dimension(pods):
     H.assert_close_dw_unit_scale(got["d_w"], ref["d_w"], H.softmax_term_magnitudes(case, grad_scale=scale))
 
 
-def test_bf16_d_not_multiple_of_64_takes_plain_path(pods):
-    case = H.loss_case(1, 3, 20, 96, 400, sigma=0.3)
+@pytest.mark.parametrize("d", [8, 72, 96, 200, 328])
+def test_bf16_d_multiple_of_8_runs_on_padded_working_copies(pods, d):
+    """bf16 with d a multiple of 8 but not of 64: the matrix-core path on working copies whose contraction length
+    is padded with zeros (a partly filled last d-tile at 328, one granule at 8)."""
+    R, T, V = 3, 150, 1500
+    case = H.loss_case(1, R, T, d, V, sigma=0.3)
+    H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case))
+    scale = float(R * case["lengths"].mean())
+    H.check_loss(H.gpu_loss(pods, torch, case, grad_scale=scale), H.oracle_loss(case, grad_scale=scale))
+    # nothing may be written past a row's d elements: a guard row and column around the outputs stay untouched
+    dv = H.to_device(case, torch)
+    dh = torch.full((R * T * d + 64,), 7.0, dtype=torch.float32, device="cuda")
+    dw = torch.full((V * d + 64,), 7.0, dtype=torch.float32, device="cuda")
+    out = dict(loss=torch.empty(1, dtype=torch.float32, device="cuda"), logp=torch.empty((R, T), dtype=torch.float32, device="cuda"),
+               d_hidden=dh[:R * T * d].view(R, T, d), d_w_lm=dw[:V * d].view(V, d))
+    pods.grpo_token_loss_fwd_bwd(dv["hidden"], dv["w"], dv["tokens"], dv["old_logp"], dv["adv"], dv["lengths"],
+                                 case["clip_eps"], 1.0, out=out)
+    torch.cuda.synchronize()
+    assert bool((dh[R * T * d:] == 7.0).all()) and bool((dw[V * d:] == 7.0).all())
+
+
+def test_bf16_d_not_multiple_of_8_takes_plain_path(pods):
+    case = H.loss_case(1, 3, 20, 100, 400, sigma=0.3)
     H.check_loss(H.gpu_loss(pods, torch, case), H.oracle_loss(case, gemm_dtype=np.float64))
 
 
