@@ -524,6 +524,12 @@ def main():
                    "arithmetic": "logits: bf16 MFMA (v_mfma_f32_32x32x16_bf16); gradients: fp16 MFMA on exact fp16 copies of "
                                  "the bf16 inputs and an fp16 softmax operand; fp32 accumulation; fp64 selector scores"},
         "roofline": head["roofline"],
+        # context, not a target and not comparable: the paper times whole training runs, never this path
+        "paper_context": "The paper reports no kernel- or stage-level timing.  Its figures are end-to-end wall-clock "
+                         "ratios to reach 0.99 x GRPO's peak test accuracy, GRPO-PODS over GRPO (Table 3): 2.0x, 3.0x, "
+                         "2.0x and 1.8x on one L40S (LoRA; Qwen2.5-3B / Llama3.2-3B on GSM8K, MATH, SciKnowEval chemistry) "
+                         "and 1.7x on 8 H100 and on 8 A100 (full-parameter, ZeRO-2; Qwen2.5-3B and 7B on GSM8K); "
+                         "precision not stated.",
         "kernels": head["kernels"],
         "selector": selector,
         "skip_zero_advantage": head["skip_zero_advantage"],
