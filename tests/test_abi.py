@@ -68,7 +68,7 @@ def test_loss_argument_checks_and_workspace_query():
 
 @pytest.mark.parametrize("shape", [(2, 64, 4096, 151936), (1, 256, 8192, 128256), (2, 64, 4096, 70000),
                                    (512, 1024, 2048, 151936), (128, 2048, 3584, 152064), (3, 50, 128, 1000),
-                                   (16, 64, 256, 1024), (1, 1, 64, 40000)])
+                                   (16, 64, 256, 1024), (1, 1, 64, 40000), (4, 300, 2080, 32000), (2, 50, 8, 700)])
 def test_workspace_layout_never_exceeds_the_workspace(shape):
     """For every workspace size from the minimum to beyond the recommendation, the arrays a call lays out
     end inside the workspace (the token block a size allows is found by search, and every array is laid out from it)."""
